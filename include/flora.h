@@ -1,0 +1,162 @@
+/*
+ * flora.h -- C ABI of the MI355X (gfx950) library for Flora's hot path
+ * (arXiv 2402.03293: random-projection compression of weight gradients).
+ *
+ * Orientation.  The paper writes the projection as A_p in R^{r x m} and
+ * compresses with G A_p^T (Algorithm 1, compression line).  This library uses
+ * A = A_p^T in R^{m x r}: for a weight W and gradient G in R^{n x m}
+ * (row-major, leading dimension m) the compressed state (the accumulator C of
+ * Algorithm 1 or the momentum M of Algorithm 2) is n x r, row-major fp32.
+ * A is never stored: every kernel regenerates the tiles it needs from the
+ * 64-bit seed (Section 2.4, "Memory analysis": only the seed is kept).
+ *
+ * The generator (the paper fixes only "N_s(0, 1/r)"; this is the library's
+ * definition, version FLORA_GENERATOR_VERSION):
+ *   words  = Philox4x32-10(counter = (j mod 2^32, q, j >> 32, 0),
+ *                          key     = (seed mod 2^32, seed >> 32))
+ *   u(x)   = ((x >> 9) + 1/2) * 2^-23                       (23 bits, never 0 or 1)
+ *   (z0,z1) = sqrt(-2 ln u(w0)) * (cos, sin)(2 pi u(w1)),  (z2,z3) likewise from (w2,w3)
+ *   A[j, 4q + i] = z_i / sqrt(r)
+ *
+ * Conventions for every entry point
+ *   - `mats` is a HOST array of `count` descriptors; every pointer inside a
+ *     descriptor is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *     grad / weight / state of one matrix must not alias.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  All work is enqueued on it; no call synchronises the device
+ *     or the stream.
+ *   - The return value is a flora_status_t.  Arguments are validated on the
+ *     host before anything is enqueued: on FLORA_ERR_INVALID or
+ *     FLORA_ERR_UNSUPPORTED nothing has been launched.
+ *   - Supported ranks: r in {8, 16, 32} (fp32 matrix cores; fp32 or bf16
+ *     gradients are used exactly) and r in {64, 128, 256} (bf16 matrix cores,
+ *     fp32 accumulation; bf16 gradients only; A and, when decompressing, the
+ *     state are rounded to bf16 on the fly).  Other r: FLORA_ERR_UNSUPPORTED.
+ *   - The library keeps a private per-device workspace (descriptor tables,
+ *     the r x r transfer matrices, statistic partials).  It grows on demand
+ *     with hipMalloc the first time a given set of descriptors is seen and is
+ *     reused afterwards; flora_shutdown() releases it.  No per-matrix state
+ *     (seed, step, epoch) is kept between calls: that lives with the caller.
+ *   - Calls on one stream execute in order.  Calls issued concurrently from
+ *     several host threads are serialised by an internal lock.
+ */
+#ifndef FLORA_H_
+#define FLORA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLORA_GENERATOR_VERSION 1
+
+typedef enum { FLORA_F32 = 0, FLORA_BF16 = 1 } flora_dtype_t;
+
+typedef enum {
+    FLORA_OK = 0,
+    FLORA_ERR_INVALID = -1,      /* null pointer, n/m/count out of range, bad enum, misaligned pointer */
+    FLORA_ERR_UNSUPPORTED = -2,  /* valid request with no kernel (rank or dtype outside the list above) */
+    FLORA_ERR_DEVICE = -3        /* a HIP call failed; see flora_last_device_error()                    */
+} flora_status_t;
+
+/* One weight matrix.  Fields a given call does not use may be NULL / 0. */
+typedef struct flora_matrix {
+    const void* grad;      /* device, n x m row-major, fp32 or bf16; read only                            */
+    void*       weight;    /* device, n x m row-major fp32; read-modify-write by the update calls        */
+    float*      state;     /* device, n x r row-major fp32: C (Algorithm 1) or M (Algorithm 2)           */
+    float*      row_stat;  /* device, n floats: factored rule's row second moment R, else NULL           */
+    float*      col_stat;  /* device, m floats: factored rule's column second moment K, else NULL        */
+    int64_t     n;         /* rows of G and W                                                            */
+    int64_t     m;         /* columns of G and W = the compressed axis = rows of A                       */
+    uint64_t    seed;      /* seed s_W of the current projection                                         */
+    uint64_t    seed_next; /* seed of the projection to move to (flora_momentum_transfer, fused step)    */
+} flora_matrix_t;
+
+typedef enum { FLORA_RULE_SGD = 0, FLORA_RULE_FACTORED = 1 } flora_rule_t;
+
+/* How the decompressed gradient Gt = alpha * state A^T is applied to W. */
+typedef struct flora_update {
+    int   rule;              /* flora_rule_t                                                            */
+    float lr;                /* learning rate eta                                                       */
+    float alpha;             /* 1/tau for Algorithm 1 (arithmetic mean over the cycle), 1 for Alg. 2    */
+    float beta2;             /* factored rule: decay of R and K (0 = plain means of this step)          */
+    float eps1;              /* factored rule: added to Gt^2                                            */
+    float clip_d;            /* factored rule: RMS clipping threshold, 0 = no clipping                  */
+    int   zero_state_after;  /* non-zero: state <- 0 once the update has read it (end of an Alg. 1 cycle) */
+} flora_update_t;
+
+/* Compression (Algorithm 1, compression line: a = b = 1;  Algorithm 2, EMA
+ * line: a = beta, b = 1 - beta):
+ *     state <- a * state + b * (grad A(seed))
+ * Uses grad, state, n, m, seed.  grad is read once, state is read and written
+ * once, nothing else is touched. */
+int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                   float a, float b, void* hip_stream);
+
+/* Decompression (Algorithm 1, decompression line, with the printed 1/n read
+ * as 1/tau; Algorithm 2, yield):
+ *     out[l] <- alpha * state A(seed)^T        (n x m, row-major, out_dtype)
+ * `out` is a HOST array of `count` DEVICE pointers.  Uses state, n, m, seed. */
+int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha,
+                     void* const* out, flora_dtype_t out_dtype, void* hip_stream);
+
+/* Momentum transfer (Algorithm 2, resample branch), computed as
+ * T = A(seed)^T A(seed_next) (r x r, in the workspace) and then
+ *     state <- state T        ( = state A(seed)^T A(seed_next) )
+ * entirely in fp32.  Uses state, n, m, seed, seed_next.  The caller replaces
+ * seed by seed_next afterwards. */
+int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream);
+
+/* Decompression fused with the base optimizer's update; Gt is never stored:
+ *   FLORA_RULE_SGD:       W <- W - lr * Gt            (Section 2.2, update rule)
+ *   FLORA_RULE_FACTORED:  the Adafactor factored second-moment rule the paper's
+ *                         experiments use as base optimizer (Section 3.1):
+ *       Q = Gt^2 + eps1;  R <- beta2 R + (1-beta2) rowmean(Q);  K likewise by column;
+ *       U = Gt / sqrt(R_i K_j / mean(R));  U <- U / max(1, RMS(U)/clip_d);  W <- W - lr U
+ *     (Gt is regenerated for each pass; row_stat and col_stat are updated in place).
+ * Uses weight, state, n, m, seed (+ row_stat, col_stat).  weight_dtype must be FLORA_F32. */
+int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
+                       const flora_update_t* u, void* hip_stream);
+
+/* One whole step of Algorithm 2 for every matrix:
+ *   if do_transfer: state <- state A(seed)^T A(seed_next) and the rest uses seed_next
+ *   state <- a * state + b * grad A;   W <- W - rule(alpha * state A^T)
+ * Equivalent to the three calls above in sequence on the same stream. */
+int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                     flora_dtype_t weight_dtype, float a, float b, int do_transfer,
+                     const flora_update_t* u, void* hip_stream);
+
+/* Test hook: writes A(seed) (m x r fp32, row-major) to A_out and/or the raw
+ * Philox words (m x ceil(r/4) x 4 uint32) to raw_out; either may be NULL.
+ * r: any multiple of 4 up to 1024.  Both are DEVICE pointers. */
+int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out,
+                         void* hip_stream);
+
+/* Host-side helper: "an independent random seed" (Algorithm 1 initialisation;
+ * Algorithm 2 resample branch) as a pure function of a global seed, the
+ * matrix's index and its resample count:
+ * first two words of Philox4x32-10(counter = (matrix_id, epoch mod 2^32, epoch >> 32, 1),
+ * key = global_seed).  Never fails. */
+uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t epoch);
+
+/* Bytes of private workspace the library would hold for this set of matrices. */
+size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
+
+/* hipError_t of the most recent failing HIP call on this thread (0 if none). */
+int flora_last_device_error(void);
+
+/* Static string for a status code. */
+const char* flora_status_string(int status);
+
+/* Frees the workspace and cached descriptor tables on every device. */
+void flora_shutdown(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int flora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLORA_H_ */

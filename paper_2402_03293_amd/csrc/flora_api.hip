@@ -1,0 +1,615 @@
+// Host side of the C ABI declared in include/flora.h: argument validation,
+// work-table construction for the grouped launches, the cached device copies
+// of descriptor tables and seeds, and the launch sequences that make up each
+// entry point.  No arithmetic of the method happens here; it all runs in the
+// gfx950 kernels.
+#include "../../include/flora.h"
+#include "flora_gen.hip.h"
+#include "flora_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+namespace flora {
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+std::mutex g_lock;
+
+#define FLORA_HIP(call)                                  \
+    do {                                                 \
+        const hipError_t e__ = (call);                   \
+        if (e__ != hipSuccess) {                         \
+            g_last_hip_error = (int)e__;                 \
+            (void)hipGetLastError();                     \
+            return FLORA_ERR_DEVICE;                     \
+        }                                                \
+    } while (0)
+
+enum Kind : int {
+    kKindCompress = 0,
+    kKindDecompress = 1,   // also SGD update: needs only the decompress table
+    kKindTransfer = 2,
+    kKindFactored = 3
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool rank_f32(int r) { return r == 8 || r == 16 || r == 32; }
+bool rank_bf16(int r) { return r == 64 || r == 128 || r == 256; }
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------ plans
+struct Plan {
+    int device = -1;
+    int kind = -1;
+    int count = 0;
+    int r = 0;
+    int variant = 0;          // compress: 0 fp32 grads, 1 bf16 grads on the fp32 path, 2 bf16 path
+    std::vector<MatDev> host_mats;      // exact copy for collision-proof comparison (device pointers unset)
+    std::vector<MatDev> dev_image;      // what was uploaded (workspace pointers filled in)
+    std::vector<WorkItem> items;        // main work table
+    std::vector<WorkItem> items2;       // transfer: state <- state T table
+    int mt = 1;                         // bf16 compress: rows per workgroup = 128 * mt
+    void* d_table = nullptr;            // MatDev[count] + items + items2
+    size_t table_cap = 0;
+    void* d_work = nullptr;             // T / statistic partials
+    size_t work_cap = 0;
+    void* h_pinned = nullptr;
+    size_t pinned_cap = 0;
+    hipEvent_t ev = nullptr;
+    hipStream_t up_stream = nullptr;
+    bool ev_pending = false;
+    uint64_t tick = 0;
+    size_t off_items = 0, off_items2 = 0, table_bytes = 0;
+};
+
+constexpr int kMaxPlans = 96;
+std::vector<Plan*> g_plans;
+uint64_t g_tick = 0;
+
+void free_plan(Plan* p)
+{
+    if (p->d_table) (void)hipFree(p->d_table);
+    if (p->d_work) (void)hipFree(p->d_work);
+    if (p->h_pinned) (void)hipHostFree(p->h_pinned);
+    if (p->ev) (void)hipEventDestroy(p->ev);
+    delete p;
+}
+
+// Work tables -----------------------------------------------------------------
+void build_compress_f32_items(Plan& p)
+{
+    std::vector<int> order(p.count);
+    for (int i = 0; i < p.count; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return p.host_mats[a].m > p.host_mats[b].m; });
+    for (int l : order) {
+        const long long n = p.host_mats[l].n;
+        int rb = 0;
+        for (long long r0 = 0; r0 < n; r0 += kCompressF32Rows, ++rb) {
+            WorkItem w{};
+            w.mat = l; w.row0 = (int)r0;
+            w.rows = (int)std::min<long long>(kCompressF32Rows, n - r0);
+            w.rblock = rb;
+            p.items.push_back(w);
+        }
+    }
+}
+
+void build_compress_bf16_items(Plan& p)
+{
+    const int S = p.r / kCompressBf16Slice;
+    // largest rows-per-workgroup that still gives the chip at least two workgroups per CU
+    int mt = 4;
+    for (; mt > 1; mt >>= 1) {
+        long long wgs = 0;
+        for (int l = 0; l < p.count; ++l) wgs += (p.host_mats[l].n + 128 * mt - 1) / (128 * mt) * S;
+        if (wgs >= 512) break;
+    }
+    p.mt = mt;
+    struct Block { int mat, row0, rows, rblock; long long m; };
+    std::vector<Block> blocks;
+    for (int l = 0; l < p.count; ++l) {
+        const long long n = p.host_mats[l].n;
+        const long long nb = (n + 128 * mt - 1) / (128 * mt);
+        long long per = (n + nb - 1) / nb;
+        per = (per + 31) / 32 * 32;
+        int rb = 0;
+        for (long long r0 = 0; r0 < n; r0 += per, ++rb)
+            blocks.push_back(Block{l, (int)r0, (int)std::min<long long>(per, n - r0), rb, p.host_mats[l].m});
+    }
+    std::stable_sort(blocks.begin(), blocks.end(), [](const Block& a, const Block& b) { return a.m > b.m; });
+    // Workgroup ids go round-robin over the 8 XCDs.  Give the S rank slices of one
+    // row block ids that are equal modulo 8, close together, so that they run on
+    // one XCD at about the same time and share its L2 copy of G.
+    for (size_t base = 0; base < blocks.size(); base += 8) {
+        const size_t nb = std::min<size_t>(8, blocks.size() - base);
+        for (int s = 0; s < S; ++s)
+            for (size_t x = 0; x < nb; ++x) {
+                const Block& b = blocks[base + x];
+                WorkItem w{};
+                w.mat = b.mat; w.row0 = b.row0; w.rows = b.rows; w.slice = s; w.rblock = b.rblock;
+                p.items.push_back(w);
+            }
+    }
+}
+
+void build_decompress_items(Plan& p)
+{
+    for (int l = 0; l < p.count; ++l) {
+        MatDev& M = p.host_mats[l];
+        M.nrowblocks = (int)((M.n + kDecompressRows - 1) / kDecompressRows);
+        M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
+        M.item0 = (int)p.items.size();
+        for (int rb = 0; rb < M.nrowblocks; ++rb)
+            for (int cc = 0; cc < M.ncolchunks; ++cc) {
+                WorkItem w{};
+                w.mat = l; w.row0 = rb * kDecompressRows;
+                w.rows = (int)std::min<long long>(kDecompressRows, M.n - w.row0);
+                w.col0 = cc * kDecompressCols; w.slice = cc; w.rblock = rb;
+                p.items.push_back(w);
+            }
+        M.nitems = (int)p.items.size() - M.item0;
+    }
+}
+
+void build_apply_T_items(Plan& p)
+{
+    for (int l = 0; l < p.count; ++l) {
+        const long long n = p.host_mats[l].n;
+        for (long long r0 = 0; r0 < n; r0 += kApplyTRows) {
+            WorkItem w{};
+            w.mat = l; w.row0 = (int)r0; w.rows = (int)std::min<long long>(kApplyTRows, n - r0);
+            p.items2.push_back(w);
+        }
+    }
+}
+
+size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r)
+{
+    size_t b = 0;
+    for (const MatDev& M : mats) {
+        if (kind == kKindTransfer) b += round_up((size_t)r * r * 4, 256);
+        if (kind == kKindFactored) {
+            b += round_up((size_t)M.ncolchunks * M.n * 4, 256);
+            b += round_up((size_t)M.nrowblocks * M.m * 4, 256);
+            b += round_up((size_t)M.nitems * 4, 256);
+            b += 256;
+        }
+    }
+    return b;
+}
+
+// How a cached plan relates to a new request with the same (kind, variant, r, count).
+enum Match : int { kExact = 0, kSeedsDiffer = 1, kPointersDiffer = 2, kShapesDiffer = 3 };
+
+Match compare(const Plan& p, const std::vector<MatDev>& mats)
+{
+    Match worst = kExact;
+    for (size_t l = 0; l < mats.size(); ++l) {
+        const MatDev& a = p.host_mats[l];
+        const MatDev& b = mats[l];
+        if (a.n != b.n || a.m != b.m) return kShapesDiffer;
+        if (a.grad != b.grad || a.weight != b.weight || a.state != b.state || a.row_stat != b.row_stat ||
+            a.col_stat != b.col_stat || a.out != b.out)
+            worst = kPointersDiffer;
+        else if (worst < kSeedsDiffer && (a.seed_lo != b.seed_lo || a.seed_hi != b.seed_hi ||
+                                          a.seedn_lo != b.seedn_lo || a.seedn_hi != b.seedn_hi))
+            worst = kSeedsDiffer;
+    }
+    return worst;
+}
+
+// Finds or creates the plan for (kind, variant, r, mats) and makes sure its device copy is
+// current on `stream`.  A request that differs from a cached plan only in seeds (a resample)
+// or only in pointers (another buffer of a ring) re-uploads the descriptor table, a few KB;
+// work tables and workspace are rebuilt only when shapes change.
+int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipStream_t stream, Plan** out)
+{
+    int device = 0;
+    FLORA_HIP(hipGetDevice(&device));
+    const int count = (int)mats.size();
+
+    Plan* best = nullptr;
+    Match best_match = kShapesDiffer;
+    int same_shape_plans = 0;
+    for (Plan* p : g_plans) {
+        if (p->device != device || p->kind != kind || p->variant != variant || p->r != r || p->count != count)
+            continue;
+        const Match mt = compare(*p, mats);
+        if (mt == kShapesDiffer) continue;
+        ++same_shape_plans;
+        if (!best || mt < best_match || (mt == best_match && p->tick < best->tick)) {
+            best = p;
+            best_match = mt;
+        }
+        if (mt == kExact) break;
+    }
+
+    if (best && best_match == kExact) {
+        best->tick = ++g_tick;
+        if (best->ev_pending && best->up_stream != stream) FLORA_HIP(hipStreamWaitEvent(stream, best->ev, 0));
+        *out = best;
+        return FLORA_OK;
+    }
+
+    Plan* p = nullptr;
+    bool keep_tables = false;
+    if (best && (best_match == kSeedsDiffer || same_shape_plans >= 16)) {
+        p = best;            // same shapes: keep its work tables and workspace
+        keep_tables = true;
+    } else {
+        if ((int)g_plans.size() >= kMaxPlans) {
+            size_t lru = 0;
+            for (size_t i = 1; i < g_plans.size(); ++i)
+                if (g_plans[i]->tick < g_plans[lru]->tick) lru = i;
+            if (g_plans[lru]->ev_pending) (void)hipEventSynchronize(g_plans[lru]->ev);
+            free_plan(g_plans[lru]);
+            g_plans.erase(g_plans.begin() + (long)lru);
+        }
+        p = new Plan();
+        g_plans.push_back(p);
+    }
+    p->device = device; p->kind = kind; p->variant = variant; p->count = count; p->r = r;
+    p->tick = ++g_tick;
+
+    if (keep_tables) {
+        for (int l = 0; l < count; ++l) {
+            MatDev M = mats[(size_t)l];
+            const MatDev& old = p->host_mats[(size_t)l];
+            M.ncolchunks = old.ncolchunks; M.nrowblocks = old.nrowblocks; M.item0 = old.item0; M.nitems = old.nitems;
+            p->host_mats[(size_t)l] = M;
+        }
+    } else {
+        p->host_mats = mats;
+        p->items.clear();
+        p->items2.clear();
+        if (kind == kKindCompress) {
+            if (variant == 2) build_compress_bf16_items(*p);
+            else build_compress_f32_items(*p);
+        } else {
+            build_decompress_items(*p);
+            if (kind == kKindTransfer) build_apply_T_items(*p);
+        }
+        p->off_items = round_up(sizeof(MatDev) * (size_t)count, 256);
+        p->off_items2 = p->off_items + round_up(sizeof(WorkItem) * p->items.size(), 256);
+        p->table_bytes = p->off_items2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
+        const size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
+        if (wbytes > 0) {
+            FLORA_HIP(hipMalloc(&p->d_work, wbytes));
+            p->work_cap = wbytes;
+        }
+        FLORA_HIP(hipMalloc(&p->d_table, p->table_bytes));
+        p->table_cap = p->table_bytes;
+        FLORA_HIP(hipHostMalloc(&p->h_pinned, p->table_bytes, hipHostMallocDefault));
+        p->pinned_cap = p->table_bytes;
+        FLORA_HIP(hipEventCreateWithFlags(&p->ev, hipEventDisableTiming));
+    }
+
+    p->dev_image = p->host_mats;
+    {
+        char* w = static_cast<char*>(p->d_work);
+        for (MatDev& M : p->dev_image) {
+            if (kind == kKindTransfer) { M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256); }
+            if (kind == kKindFactored) {
+                M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * M.n * 4, 256);
+                M.colpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.nrowblocks * M.m * 4, 256);
+                M.itempart = reinterpret_cast<float*>(w); w += round_up((size_t)M.nitems * 4, 256);
+                M.scal = reinterpret_cast<float*>(w); w += 256;
+            }
+        }
+    }
+
+    // The pinned staging copy may still be the source of the previous upload.
+    if (p->ev_pending) { FLORA_HIP(hipEventSynchronize(p->ev)); p->ev_pending = false; }
+    char* hp = static_cast<char*>(p->h_pinned);
+    std::memcpy(hp, p->dev_image.data(), sizeof(MatDev) * (size_t)count);
+    size_t upload = sizeof(MatDev) * (size_t)count;
+    if (!keep_tables) {
+        if (!p->items.empty()) std::memcpy(hp + p->off_items, p->items.data(), sizeof(WorkItem) * p->items.size());
+        if (!p->items2.empty()) std::memcpy(hp + p->off_items2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
+        upload = p->table_bytes;
+    }
+    FLORA_HIP(hipMemcpyAsync(p->d_table, p->h_pinned, upload, hipMemcpyHostToDevice, stream));
+    FLORA_HIP(hipEventRecord(p->ev, stream));
+    p->ev_pending = true;
+    p->up_stream = stream;
+    *out = p;
+    return FLORA_OK;
+}
+
+// ------------------------------------------------------------- validation
+int check_common(const flora_matrix_t* mats, int count, int r)
+{
+    if (count < 0) return FLORA_ERR_INVALID;
+    if (count > 0 && !mats) return FLORA_ERR_INVALID;
+    if (r <= 0) return FLORA_ERR_INVALID;
+    if (!rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
+    for (int l = 0; l < count; ++l) {
+        if (mats[l].n < 1 || mats[l].m < 1) return FLORA_ERR_INVALID;
+        if (mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > 0x7fffffffLL - 1024) return FLORA_ERR_INVALID;
+        if (!mats[l].state || !aligned16(mats[l].state)) return FLORA_ERR_INVALID;
+    }
+    return FLORA_OK;
+}
+
+bool dtype_ok(int d) { return d == FLORA_F32 || d == FLORA_BF16; }
+
+}  // namespace
+
+}  // namespace flora
+
+using namespace flora;
+
+// The seeds ride in the MatDev table (they are part of what is hashed), so a new seed means
+// a table upload of a few KB on the caller's stream; pointers, shapes and work tables are
+// rebuilt only when the shapes change.
+static void fill_seed(MatDev& M, const flora_matrix_t& f)
+{
+    M.seed_lo = (uint32_t)(f.seed & 0xffffffffu);
+    M.seed_hi = (uint32_t)(f.seed >> 32);
+    M.seedn_lo = (uint32_t)(f.seed_next & 0xffffffffu);
+    M.seedn_hi = (uint32_t)(f.seed_next >> 32);
+}
+
+extern "C" {
+
+int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                   float a, float b, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
+            return FLORA_ERR_INVALID;
+    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
+    if (count == 0) return FLORA_OK;
+
+    std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.grad = mats[l].grad; M.state = mats[l].state; M.n = mats[l].n; M.m = mats[l].m;
+        fill_seed(M, mats[l]);
+        M.seedn_lo = M.seedn_hi = 0;
+        md[(size_t)l] = M;
+    }
+    const int variant = rank_bf16(r) ? 2 : (grad_dtype == FLORA_BF16 ? 1 : 0);
+    Plan* p = nullptr;
+    st = get_plan(kKindCompress, variant, r, md, s, &p);
+    if (st != FLORA_OK) return st;
+    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
+    if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), r, p->mt, a, b, s));
+    else FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), r, variant == 1, a, b, s));
+    return FLORA_OK;
+}
+
+static int run_decompress(Plan* p, int r, int mode, int out_bf16, DecompressParams dp, hipStream_t s)
+{
+    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
+    if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), r, mode, out_bf16, dp, s));
+    else FLORA_HIP(launch_decompress_f32(dm, di, (int)p->items.size(), r, mode, out_bf16, dp, s));
+    return FLORA_OK;
+}
+
+int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
+                     flora_dtype_t out_dtype, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (!dtype_ok((int)out_dtype)) return FLORA_ERR_INVALID;
+    if (count > 0 && !out) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!out[l] || !aligned16(out[l]) || out[l] == (void*)mats[l].state) return FLORA_ERR_INVALID;
+    if (count == 0) return FLORA_OK;
+
+    std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.state = mats[l].state; M.out = out[l]; M.n = mats[l].n; M.m = mats[l].m;
+        fill_seed(M, mats[l]);
+        M.seedn_lo = M.seedn_hi = 0;
+        md[(size_t)l] = M;
+    }
+    Plan* p = nullptr;
+    st = get_plan(kKindDecompress, out_dtype == FLORA_BF16 ? 1 : 0, r, md, s, &p);
+    if (st != FLORA_OK) return st;
+    DecompressParams dp{alpha, 0.f};
+    return run_decompress(p, r, kModeOut, out_dtype == FLORA_BF16, dp, s);
+}
+
+int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (count == 0) return FLORA_OK;
+
+    std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.state = mats[l].state; M.n = mats[l].n; M.m = mats[l].m;
+        fill_seed(M, mats[l]);
+        md[(size_t)l] = M;
+    }
+    Plan* p = nullptr;
+    st = get_plan(kKindTransfer, 0, r, md, s, &p);
+    if (st != FLORA_OK) return st;
+    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    const WorkItem* di2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items2);
+    FLORA_HIP(launch_transfer_T(dm, count, r, s));
+    FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, s));
+    return FLORA_OK;
+}
+
+static int check_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
+                        const flora_update_t* u)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (!u) return FLORA_ERR_INVALID;
+    if (!dtype_ok((int)weight_dtype)) return FLORA_ERR_INVALID;
+    if (u->rule != FLORA_RULE_SGD && u->rule != FLORA_RULE_FACTORED) return FLORA_ERR_INVALID;
+    if (u->rule == FLORA_RULE_FACTORED &&
+        (!(u->beta2 >= 0.f && u->beta2 <= 1.f) || !(u->clip_d >= 0.f) || !(u->eps1 >= 0.f)))
+        return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l) {
+        if (!mats[l].weight || !aligned16(mats[l].weight) || mats[l].weight == (void*)mats[l].state)
+            return FLORA_ERR_INVALID;
+        if (u->rule == FLORA_RULE_FACTORED &&
+            (!mats[l].row_stat || !mats[l].col_stat || !aligned16(mats[l].row_stat) || !aligned16(mats[l].col_stat)))
+            return FLORA_ERR_INVALID;
+    }
+    if (weight_dtype != FLORA_F32) return FLORA_ERR_UNSUPPORTED;
+    return FLORA_OK;
+}
+
+static int apply_update_locked(const flora_matrix_t* mats, int count, int r, const flora_update_t* u,
+                               bool use_seed_next, hipStream_t s)
+{
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.weight = static_cast<float*>(mats[l].weight); M.state = mats[l].state;
+        M.n = mats[l].n; M.m = mats[l].m;
+        if (u->rule == FLORA_RULE_FACTORED) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
+        fill_seed(M, mats[l]);
+        if (use_seed_next) { M.seed_lo = M.seedn_lo; M.seed_hi = M.seedn_hi; }
+        M.seedn_lo = M.seedn_hi = 0;
+        md[(size_t)l] = M;
+    }
+    Plan* p = nullptr;
+    const int kind = (u->rule == FLORA_RULE_FACTORED) ? kKindFactored : kKindDecompress;
+    int st = get_plan(kind, 2, r, md, s, &p);
+    if (st != FLORA_OK) return st;
+    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    if (u->rule == FLORA_RULE_SGD) {
+        DecompressParams dp{u->alpha, u->lr * u->alpha};
+        st = run_decompress(p, r, kModeSgd, 0, dp, s);
+        if (st != FLORA_OK) return st;
+    } else {
+        DecompressParams dp{u->alpha, u->lr};
+        st = run_decompress(p, r, kModeStats, 0, dp, s);
+        if (st != FLORA_OK) return st;
+        FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
+        if (u->clip_d > 0.f) {
+            st = run_decompress(p, r, kModeRms, 0, dp, s);
+            if (st != FLORA_OK) return st;
+            FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, s));
+        }
+        st = run_decompress(p, r, kModeFactored, 0, dp, s);
+        if (st != FLORA_OK) return st;
+    }
+    if (u->zero_state_after) FLORA_HIP(launch_zero_state(dm, count, r, s));
+    return FLORA_OK;
+}
+
+int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
+                       const flora_update_t* u, void* hip_stream)
+{
+    int st = check_update(mats, count, r, weight_dtype, u);
+    if (st != FLORA_OK) return st;
+    if (count == 0) return FLORA_OK;
+    std::lock_guard<std::mutex> guard(g_lock);
+    return apply_update_locked(mats, count, r, u, false, static_cast<hipStream_t>(hip_stream));
+}
+
+int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                     flora_dtype_t weight_dtype, float a, float b, int do_transfer,
+                     const flora_update_t* u, void* hip_stream)
+{
+    int st = check_update(mats, count, r, weight_dtype, u);
+    if (st != FLORA_OK) return st;
+    if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
+            return FLORA_ERR_INVALID;
+    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
+    if (count == 0) return FLORA_OK;
+
+    if (do_transfer) {
+        st = flora_momentum_transfer(mats, count, r, hip_stream);
+        if (st != FLORA_OK) return st;
+    }
+    std::vector<flora_matrix_t> cur(mats, mats + count);
+    if (do_transfer)
+        for (auto& f : cur) f.seed = f.seed_next;
+    st = flora_compress(cur.data(), count, r, grad_dtype, a, b, hip_stream);
+    if (st != FLORA_OK) return st;
+    return flora_apply_update(cur.data(), count, r, weight_dtype, u, hip_stream);
+}
+
+int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out, void* hip_stream)
+{
+    if (m < 0 || r <= 0 || (r % 4) != 0 || r > 1024) return FLORA_ERR_INVALID;
+    if ((A_out && !aligned16(A_out)) || (raw_out && !aligned16(raw_out))) return FLORA_ERR_INVALID;
+    if (m == 0 || (!A_out && !raw_out)) return FLORA_OK;
+    FLORA_HIP(launch_debug_generate(seed, (long long)m, r, A_out, raw_out, static_cast<hipStream_t>(hip_stream)));
+    return FLORA_OK;
+}
+
+uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t epoch)
+{
+    const Words4 x = philox4x32_10((uint32_t)matrix_id, (uint32_t)(epoch & 0xffffffffu), (uint32_t)(epoch >> 32),
+                                   kDomainSeed, (uint32_t)(global_seed & 0xffffffffu),
+                                   (uint32_t)(global_seed >> 32));
+    return (uint64_t)x.w[0] | ((uint64_t)x.w[1] << 32);
+}
+
+size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
+{
+    if (!mats || count <= 0 || r <= 0) return 0;
+    std::vector<MatDev> md((size_t)count);
+    size_t items = 0;
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.n = mats[l].n; M.m = mats[l].m;
+        if (M.n < 1 || M.m < 1) return 0;
+        M.nrowblocks = (int)((M.n + kDecompressRows - 1) / kDecompressRows);
+        M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
+        M.nitems = M.nrowblocks * M.ncolchunks;
+        items += (size_t)M.nitems;
+        md[(size_t)l] = M;
+    }
+    return workspace_bytes_for(md, kKindTransfer, r) + workspace_bytes_for(md, kKindFactored, r) +
+           sizeof(MatDev) * (size_t)count + sizeof(WorkItem) * items;
+}
+
+int flora_last_device_error(void) { return g_last_hip_error; }
+
+const char* flora_status_string(int status)
+{
+    switch (status) {
+    case FLORA_OK: return "ok";
+    case FLORA_ERR_INVALID: return "invalid argument";
+    case FLORA_ERR_UNSUPPORTED: return "unsupported rank or dtype";
+    case FLORA_ERR_DEVICE: return "HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+void flora_shutdown(void)
+{
+    std::lock_guard<std::mutex> guard(g_lock);
+    for (Plan* p : g_plans) {
+        if (p->ev_pending) (void)hipEventSynchronize(p->ev);
+        free_plan(p);
+    }
+    g_plans.clear();
+}
+
+int flora_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Small grouped kernels around the factored second-moment rule (the Adafactor
+// rule the paper uses as base optimizer, Section 3.1) and the end of an
+// accumulation cycle (Algorithm 1: the accumulator starts each cycle at zero).
+// All reductions run in a fixed order, so results are reproducible bit for bit.
+#include "flora_internal.h"
+
+namespace flora {
+
+namespace {
+
+__device__ __forceinline__ float block_sum_256(float v, float* lds)
+{
+    const int tid = threadIdx.x;
+    lds[tid] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) lds[tid] += lds[tid + s];
+        __syncthreads();
+    }
+    const float r = lds[0];
+    __syncthreads();
+    return r;
+}
+
+// R_i <- beta2 R_i + (1 - beta2) (rowmean(Gt^2) + eps1), K_j likewise by column,
+// scal[0] <- mean(R), scal[1] <- 1 (no clipping until rms_finalize says otherwise).
+__global__ __launch_bounds__(256) void stats_finalize_kernel(const MatDev* __restrict__ mats,
+                                                             float beta2, float eps1)
+{
+    __shared__ float lds[256];
+    const MatDev& M = mats[blockIdx.x];
+    const long long n = M.n, m = M.m;
+    const int tid = threadIdx.x;
+    float rsum = 0.f;
+    for (long long i = tid; i < n; i += 256) {
+        float s = 0.f;
+        for (int c = 0; c < M.ncolchunks; ++c) s += M.rowpart[(long long)c * n + i];
+        const float r = beta2 * M.row_stat[i] + (1.f - beta2) * (s / (float)m + eps1);
+        M.row_stat[i] = r;
+        rsum += r;
+    }
+    for (long long j = tid; j < m; j += 256) {
+        float s = 0.f;
+        for (int b = 0; b < M.nrowblocks; ++b) s += M.colpart[(long long)b * m + j];
+        M.col_stat[j] = beta2 * M.col_stat[j] + (1.f - beta2) * (s / (float)n + eps1);
+    }
+    const float tot = block_sum_256(rsum, lds);
+    if (tid == 0) {
+        M.scal[0] = tot / (float)n;
+        M.scal[1] = 1.f;
+    }
+}
+
+// scal[1] <- 1 / max(1, RMS(U) / clip_d), RMS(U)^2 = sum of the workgroup partials / (n m)
+__global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restrict__ mats, float clip_d)
+{
+    __shared__ float lds[256];
+    const MatDev& M = mats[blockIdx.x];
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    for (int i = tid; i < M.nitems; i += 256) s += M.itempart[i];
+    const float tot = block_sum_256(s, lds);
+    if (tid == 0) {
+        const float rms = sqrtf(tot / ((float)M.n * (float)M.m));
+        const float d = rms / clip_d;
+        M.scal[1] = 1.f / (d > 1.f ? d : 1.f);
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_state_kernel(const MatDev* __restrict__ mats, int r)
+{
+    const MatDev& M = mats[blockIdx.y];
+    const long long total4 = (M.n * r) >> 2;   // r is a multiple of 4
+    float4* p = reinterpret_cast<float4*>(M.state);
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total4; i += (long long)gridDim.x * 256)
+        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+}  // namespace
+
+hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, beta2, eps1);
+    return hipGetLastError();
+}
+
+hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(rms_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, clip_d);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_state_kernel, dim3(16, (unsigned)count), dim3(256), 0, s, mats, r);
+    return hipGetLastError();
+}
+
+}  // namespace flora

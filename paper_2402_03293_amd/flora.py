@@ -1,0 +1,204 @@
+"""ctypes binding of libflora.so (include/flora.h): argument marshalling only.
+
+Every step of the method runs in the HIP kernels behind the C ABI.  PyTorch is
+used by callers for device memory and streams; this module only needs
+``tensor.data_ptr()`` and a stream handle.  There is no CPU fallback: if the
+library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Sequence
+
+F32 = 0
+BF16 = 1
+OK = 0
+ERR_INVALID = -1
+ERR_UNSUPPORTED = -2
+ERR_DEVICE = -3
+RULE_SGD = 0
+RULE_FACTORED = 1
+
+_LIB_PATH = Path(__file__).resolve().parent / "libflora.so"
+
+
+class Matrix(ctypes.Structure):
+    """flora_matrix_t"""
+    _fields_ = [
+        ("grad", ctypes.c_void_p),
+        ("weight", ctypes.c_void_p),
+        ("state", ctypes.c_void_p),
+        ("row_stat", ctypes.c_void_p),
+        ("col_stat", ctypes.c_void_p),
+        ("n", ctypes.c_int64),
+        ("m", ctypes.c_int64),
+        ("seed", ctypes.c_uint64),
+        ("seed_next", ctypes.c_uint64),
+    ]
+
+
+class Update(ctypes.Structure):
+    """flora_update_t"""
+    _fields_ = [
+        ("rule", ctypes.c_int),
+        ("lr", ctypes.c_float),
+        ("alpha", ctypes.c_float),
+        ("beta2", ctypes.c_float),
+        ("eps1", ctypes.c_float),
+        ("clip_d", ctypes.c_float),
+        ("zero_state_after", ctypes.c_int),
+    ]
+
+
+class FloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().flora_status_string(status).decode()
+        extra = ""
+        if status == ERR_DEVICE:
+            extra = " (hipError %d)" % lib().flora_last_device_error()
+        super().__init__("%s: %s%s" % (where, msg, extra))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise ImportError(
+                "libflora.so is missing at %s: build it with "
+                "`python -m paper_2402_03293_amd.build` (needs hipcc)" % _LIB_PATH)
+        L = ctypes.CDLL(str(_LIB_PATH))
+        MP = ctypes.POINTER(Matrix)
+        vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.flora_compress.argtypes = [MP, ci, ci, ci, cf, cf, vp]
+        L.flora_compress.restype = ci
+        L.flora_decompress.argtypes = [MP, ci, ci, cf, ctypes.POINTER(vp), ci, vp]
+        L.flora_decompress.restype = ci
+        L.flora_momentum_transfer.argtypes = [MP, ci, ci, vp]
+        L.flora_momentum_transfer.restype = ci
+        L.flora_apply_update.argtypes = [MP, ci, ci, ci, ctypes.POINTER(Update), vp]
+        L.flora_apply_update.restype = ci
+        L.flora_fused_step.argtypes = [MP, ci, ci, ci, ci, cf, cf, ci, ctypes.POINTER(Update), vp]
+        L.flora_fused_step.restype = ci
+        L.flora_debug_generate.argtypes = [ctypes.c_uint64, ctypes.c_int64, ci, vp, vp, vp]
+        L.flora_debug_generate.restype = ci
+        L.flora_derive_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
+        L.flora_derive_seed.restype = ctypes.c_uint64
+        L.flora_workspace_bytes.argtypes = [MP, ci, ci]
+        L.flora_workspace_bytes.restype = ctypes.c_size_t
+        L.flora_last_device_error.argtypes = []
+        L.flora_last_device_error.restype = ci
+        L.flora_status_string.argtypes = [ci]
+        L.flora_status_string.restype = ctypes.c_char_p
+        L.flora_shutdown.argtypes = []
+        L.flora_shutdown.restype = None
+        L.flora_version.argtypes = []
+        L.flora_version.restype = ci
+        _lib = L
+    return _lib
+
+
+EXPORTS = [
+    "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_apply_update",
+    "flora_fused_step", "flora_debug_generate", "flora_derive_seed", "flora_workspace_bytes",
+    "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
+]
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def matrices(n_m: Sequence, grads=None, weights=None, states=None, row_stats=None, col_stats=None,
+             seeds=None, seeds_next=None):
+    """Builds a ctypes array of flora_matrix_t.  Each argument is a sequence of
+    torch tensors (or raw device addresses) or None."""
+    count = len(n_m)
+    arr = (Matrix * count)()
+    for l, (n, m) in enumerate(n_m):
+        arr[l].n, arr[l].m = int(n), int(m)
+        arr[l].grad = _ptr(grads[l]) if grads is not None else None
+        arr[l].weight = _ptr(weights[l]) if weights is not None else None
+        arr[l].state = _ptr(states[l]) if states is not None else None
+        arr[l].row_stat = _ptr(row_stats[l]) if row_stats is not None else None
+        arr[l].col_stat = _ptr(col_stats[l]) if col_stats is not None else None
+        arr[l].seed = int(seeds[l]) if seeds is not None else 0
+        arr[l].seed_next = int(seeds_next[l]) if seeds_next is not None else 0
+    return arr
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise FloraError(status, where)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None          # torch.cuda.Stream
+
+
+def compress(mats, r: int, grad_dtype: int, a: float = 1.0, b: float = 1.0, stream=None):
+    _check(lib().flora_compress(mats, len(mats), r, grad_dtype, a, b, _stream(stream)), "flora_compress")
+
+
+def decompress(mats, r: int, alpha: float, outs, out_dtype: int, stream=None):
+    count = len(mats)
+    arr = (ctypes.c_void_p * count)(*[_ptr(o) for o in outs])
+    _check(lib().flora_decompress(mats, count, r, alpha, arr, out_dtype, _stream(stream)), "flora_decompress")
+
+
+def momentum_transfer(mats, r: int, stream=None):
+    _check(lib().flora_momentum_transfer(mats, len(mats), r, _stream(stream)), "flora_momentum_transfer")
+
+
+def apply_update(mats, r: int, weight_dtype: int, update: Update, stream=None):
+    _check(lib().flora_apply_update(mats, len(mats), r, weight_dtype, ctypes.byref(update), _stream(stream)),
+           "flora_apply_update")
+
+
+def fused_step(mats, r: int, grad_dtype: int, weight_dtype: int, a: float, b: float, do_transfer: bool,
+               update: Update, stream=None):
+    _check(lib().flora_fused_step(mats, len(mats), r, grad_dtype, weight_dtype, a, b, int(do_transfer),
+                                  ctypes.byref(update), _stream(stream)), "flora_fused_step")
+
+
+def debug_generate(seed: int, m: int, r: int, A_out=None, raw_out=None, stream=None):
+    _check(lib().flora_debug_generate(seed, m, r, _ptr(A_out), _ptr(raw_out), _stream(stream)),
+           "flora_debug_generate")
+
+
+def derive_seed(global_seed: int, matrix_id: int, epoch: int) -> int:
+    return int(lib().flora_derive_seed(global_seed, matrix_id, epoch))
+
+
+def workspace_bytes(mats, r: int) -> int:
+    return int(lib().flora_workspace_bytes(mats, len(mats), r))
+
+
+def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False) -> Update:
+    return Update(RULE_SGD, lr, alpha, 0.0, 0.0, 0.0, int(zero_state_after))
+
+
+def factored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
+                    zero_state_after: bool = False) -> Update:
+    return Update(RULE_FACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after))
+
+
+def shutdown():
+    lib().flora_shutdown()
+
+
+def version() -> int:
+    return lib().flora_version()

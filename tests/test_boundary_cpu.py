@@ -1,0 +1,131 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every
+function include/flora.h declares, and rejects bad arguments on the host
+before anything could be launched (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_03293_amd import flora, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "flora.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(flora_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 12
+    L = flora.lib()
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(flora.EXPORTS) == names
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(flora.Matrix) == 5 * 8 + 2 * 8 + 2 * 8
+    assert ctypes.sizeof(flora.Update) == 7 * 4
+
+
+def test_status_strings_and_version():
+    L = flora.lib()
+    assert L.flora_status_string(0) == b"ok"
+    assert b"invalid" in L.flora_status_string(-1)
+    assert b"unsupported" in L.flora_status_string(-2)
+    assert flora.version() >= 100
+
+
+def _mats(n=16, m=16, grad=0x1000, weight=0x2000, state=0x3000, rs=None, cs=None):
+    # fake, aligned, non-null device addresses: validation never dereferences them
+    return flora.matrices([(n, m)], grads=[grad], weights=[weight], states=[state],
+                          row_stats=[rs] if rs else None, col_stats=[cs] if cs else None, seeds=[1])
+
+
+def test_compress_validation():
+    L = flora.lib()
+    ok = _mats()
+    assert L.flora_compress(None, 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(ok, -1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(ok, 1, 0, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(ok, 1, 12, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_compress(ok, 1, 512, flora.BF16, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_compress(ok, 1, 64, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_compress(ok, 1, 16, 7, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(_mats(n=0), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(_mats(m=-3), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(_mats(grad=0x1004), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(_mats(state=0x3008), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(_mats(grad=0x3000), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    nog = flora.matrices([(16, 16)], states=[0x3000], seeds=[1])
+    assert L.flora_compress(nog, 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress(ok, 0, 16, flora.F32, 1.0, 1.0, None) == flora.OK      # empty set
+
+
+def test_decompress_and_transfer_validation():
+    L = flora.lib()
+    ok = _mats()
+    out = (ctypes.c_void_p * 1)(0x4000)
+    assert L.flora_decompress(ok, 1, 16, 1.0, None, flora.F32, None) == flora.ERR_INVALID
+    assert L.flora_decompress(ok, 1, 16, 1.0, (ctypes.c_void_p * 1)(None), flora.F32, None) == flora.ERR_INVALID
+    assert L.flora_decompress(ok, 1, 16, 1.0, (ctypes.c_void_p * 1)(0x4002), flora.F32, None) == flora.ERR_INVALID
+    assert L.flora_decompress(ok, 1, 16, 1.0, out, 9, None) == flora.ERR_INVALID
+    assert L.flora_decompress(ok, 1, 20, 1.0, out, flora.F32, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_decompress(ok, 0, 16, 1.0, None, flora.F32, None) == flora.OK
+    assert L.flora_momentum_transfer(None, 2, 16, None) == flora.ERR_INVALID
+    assert L.flora_momentum_transfer(ok, 1, 3, None) == flora.ERR_UNSUPPORTED
+    nos = flora.matrices([(16, 16)], seeds=[1])
+    assert L.flora_momentum_transfer(nos, 1, 16, None) == flora.ERR_INVALID
+
+
+def test_update_validation():
+    L = flora.lib()
+    ok = _mats()
+    sgd = flora.sgd_update(0.1)
+    assert L.flora_apply_update(ok, 1, 16, flora.F32, None, None) == flora.ERR_INVALID
+    assert L.flora_apply_update(ok, 1, 16, flora.BF16, ctypes.byref(sgd), None) == flora.ERR_UNSUPPORTED
+    assert L.flora_apply_update(ok, 1, 16, 5, ctypes.byref(sgd), None) == flora.ERR_INVALID
+    bad_rule = flora.Update(9, 0.1, 1.0, 0, 0, 0, 0)
+    assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(bad_rule), None) == flora.ERR_INVALID
+    fac = flora.factored_update(0.1, 1.0, 0.0, 1e-30, 1.0)
+    assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(fac), None) == flora.ERR_INVALID  # no R, K
+    neg = flora.factored_update(0.1, 1.0, 1.5, 1e-30, 1.0)
+    assert L.flora_apply_update(_mats(rs=0x5000, cs=0x6000), 1, 16, flora.F32, ctypes.byref(neg), None) \
+        == flora.ERR_INVALID
+    now = flora.matrices([(16, 16)], states=[0x3000], seeds=[1])
+    assert L.flora_apply_update(now, 1, 16, flora.F32, ctypes.byref(sgd), None) == flora.ERR_INVALID
+    assert L.flora_fused_step(ok, 1, 64, flora.F32, flora.F32, 0.9, 0.1, 0, ctypes.byref(sgd), None) \
+        == flora.ERR_UNSUPPORTED
+    assert L.flora_fused_step(ok, 0, 64, flora.BF16, flora.F32, 0.9, 0.1, 0, ctypes.byref(sgd), None) == flora.OK
+
+
+def test_debug_generate_validation():
+    L = flora.lib()
+    assert L.flora_debug_generate(1, -1, 16, None, None, None) == flora.ERR_INVALID
+    assert L.flora_debug_generate(1, 8, 6, 0x1000, None, None) == flora.ERR_INVALID
+    assert L.flora_debug_generate(1, 8, 2048, 0x1000, None, None) == flora.ERR_INVALID
+    assert L.flora_debug_generate(1, 8, 16, 0x1004, None, None) == flora.ERR_INVALID
+    assert L.flora_debug_generate(1, 0, 16, 0x1000, None, None) == flora.OK
+    assert L.flora_debug_generate(1, 8, 16, None, None, None) == flora.OK
+
+
+def test_workspace_query_and_seed_helper_are_host_only():
+    wl = workloads.workload(2)
+    mats = flora.matrices(wl.shapes)
+    b = flora.workspace_bytes(mats, wl.r)
+    assert 0 < b < 64 << 20
+    assert flora.workspace_bytes(mats, 0) == 0
+    s = {flora.derive_seed(7, l, e) for l in range(30) for e in range(30)}
+    assert len(s) == 900
+
+
+def test_workload_tallies_match_the_configurations():
+    want = {1: (1, 65536), 2: (96, 44040192), 3: (48, 84934656), 4: (384, 2818572288), 5: (192, 1474560000)}
+    for i, (cnt, el) in want.items():
+        wl = workloads.workload(i)
+        assert (len(wl.shapes), wl.elements) == (cnt, el)
+    assert workloads.workload(4).state_elements * 4 == 1384120320
