@@ -1,0 +1,301 @@
+#!/usr/bin/env python3
+"""Benchmark of Flora's hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+  * Algorithm-1 workloads (1, 2, 4): one accumulation cycle = tau grouped compress
+    launches over tau distinct gradient sets, then decompress + update (+ state reset),
+    then a new seed per matrix.
+  * Algorithm-2 workloads (3, 5): one optimizer step = (transfer when t = 0 mod kappa)
+    + EMA compress + decompress + SGD update.
+The default workload is configuration 2 of the benchmark spec (T5-small shapes, fp32, r = 16,
+tau = 8), the one the headline metric is quoted on.  Inputs are resident in HBM before the
+timed region starts; gradient sets rotate so that no set is re-read from cache.
+
+Prints ONE JSON line (see the keys below); --gpus above 1 is refused: this build is
+single-GPU by design.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--grad-sets", type=int, default=None, help="distinct gradient sets in the ring")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
+                    help="size of the oracle's sample (fp64 GFLOP)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on one GPU only (no collectives are part of it); "
+                         "--gpus %d is not supported, use --gpus 1\n" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2402_03293_amd import flora, workloads
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(1)
+    flora.lib()                       # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    wl = workloads.workload(args.config)
+    r = wl.r
+    shapes = wl.shapes
+    count = len(shapes)
+    gdt = flora.F32 if wl.grad_dtype == "f32" else flora.BF16
+    gbytes = 4 if wl.grad_dtype == "f32" else 2
+
+    default_steps = {1: 500, 2: 200, 3: 300, 4: 3, 5: 40}[wl.index]
+    default_warm = {1: 20, 2: 10, 3: 10, 4: 1, 5: 3}[wl.index]
+    steps = args.steps if args.steps is not None else default_steps
+    warmup = args.warmup if args.warmup is not None else default_warm
+
+    # ---- inputs, resident in HBM -------------------------------------------------
+    gen = workloads.make_generator(wl.seed, dev)
+    if args.grad_sets is not None:
+        nsets = args.grad_sets
+    elif wl.algorithm == 1:
+        nsets = wl.tau if wl.index != 4 else 4
+    else:
+        nsets = max(4, min(8, int(2e9 // max(1, wl.grad_bytes)) + 1))
+    grad_sets = [workloads.make_grad_set(wl, gen, dev) for _ in range(nsets)]
+    W = workloads.make_weight_set(wl, gen, dev)
+    states = [torch.zeros((n, r), device=dev, dtype=torch.float32) for n, _ in shapes]
+    row_stats = col_stats = None
+    if wl.rule == "factored":
+        row_stats = [torch.zeros((n,), device=dev) for n, _ in shapes]
+        col_stats = [torch.zeros((m,), device=dev) for _, m in shapes]
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    gseed = 1234
+    epoch = 0
+    seeds = flora.derive_seeds(gseed, 0, count, epoch)
+
+    # one descriptor array per gradient set, built once; only the seed fields change later
+    mats_sets = [flora.matrices(shapes, grads=grad_sets[g], weights=W, states=states, row_stats=row_stats,
+                                col_stats=col_stats, seeds=seeds, seeds_next=seeds) for g in range(nsets)]
+    views = [flora.fields(mt) for mt in mats_sets]
+
+    def set_seeds(cur, nxt=None):
+        for v in views:
+            v["seed"][:] = cur
+            v["seed_next"][:] = cur if nxt is None else nxt
+
+    if wl.rule == "factored":
+        ex = wl.extra
+        upd = flora.factored_update(wl.lr, 1.0 / wl.tau, ex["beta2"], ex["eps1"], ex["clip_d"],
+                                    zero_state_after=True)
+    elif wl.algorithm == 1:
+        upd = flora.sgd_update(wl.lr, 1.0 / wl.tau, zero_state_after=True)
+    else:
+        upd = flora.sgd_update(wl.lr, 1.0)
+
+    ev_pairs = {"compress": [], "update": [], "transfer": []}
+    record = {"on": False}
+
+    def timed(kind, fn):
+        if record["on"]:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            ev_pairs[kind].append((e0, e1))
+        else:
+            fn()
+
+    tstate = {"t": 0, "gi": 0}
+
+    def one_step():
+        nonlocal seeds, epoch
+        if wl.algorithm == 1:
+            for _ in range(wl.tau):
+                mt = mats_sets[tstate["gi"] % nsets]
+                tstate["gi"] += 1
+                timed("compress", lambda: flora.compress(mt, r, gdt, 1.0, 1.0, stream))
+            mt = mats_sets[0]
+            timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
+            epoch += 1
+            seeds = flora.derive_seeds(gseed, 0, count, epoch)
+            set_seeds(seeds)
+        else:
+            t = tstate["t"]
+            if t % wl.kappa == 0:
+                epoch += 1
+                nxt = flora.derive_seeds(gseed, 0, count, epoch)
+                set_seeds(seeds, nxt)
+                mt = mats_sets[0]
+                timed("transfer", lambda: flora.momentum_transfer(mt, r, stream))
+                seeds = nxt
+                set_seeds(seeds)
+            mt = mats_sets[tstate["gi"] % nsets]
+            tstate["gi"] += 1
+            timed("compress", lambda: flora.compress(mt, r, gdt, wl.beta, 1.0 - wl.beta, stream))
+            timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
+            tstate["t"] += 1
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    record["on"] = True
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    record["on"] = False
+    elapsed = t1 - t0
+
+    grads_per_step = wl.tau if wl.algorithm == 1 else 1
+    grad_bytes_step = wl.elements * gbytes * grads_per_step
+    value = grad_bytes_step * steps / elapsed / 1e9
+
+    # ---- per-kernel launch durations from the events of the timed region -------------
+    E, S = wl.elements, wl.state_elements
+    alg_bytes = {
+        "compress": gbytes * E + 8 * S,
+        "update": 4 * S + 8 * E if wl.rule == "sgd" else (3 * 4 * S + 8 * E),
+        "transfer": 8 * S,
+    }
+    alg_flops = {"compress": 2.0 * E * r, "update": 2.0 * E * r * (1 if wl.rule == "sgd" else 3),
+                 "transfer": sum(2.0 * m * r * r + 2.0 * n * r * r for n, m in shapes)}
+    kern = {}
+    for k, pairs in ev_pairs.items():
+        if not pairs:
+            continue
+        ms = [a.elapsed_time(b) for a, b in pairs]
+        avg = sum(ms) / len(ms)
+        kern[k] = {
+            "launches": len(ms), "avg_ms": avg, "min_ms": min(ms),
+            "alg_GBps": alg_bytes[k] / (avg * 1e-3) / 1e9,
+            "alg_TFLOPs": alg_flops[k] / (avg * 1e-3) / 1e12,
+        }
+    dominant = max((k for k in kern if k != "transfer"), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
+    dk = kern[dominant]
+    roofline = {
+        "kernel": {"compress": "compress (state <- a*state + b*G*A)",
+                   "update": "decompress + update (W <- W - rule(alpha*state*A^T))"}[dominant],
+        "bound": "hbm", "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": dk["alg_GBps"] / HBM_PEAK_GBS, "traffic": None,
+        "bytes_per_launch": alg_bytes[dominant], "avg_launch_ms": dk["avg_ms"],
+    }
+    if r >= 64:
+        roofline["mfma_frac_of_bf16_peak"] = dk["alg_TFLOPs"] / BF16_MFMA_PEAK_TFLOPS
+
+    out = {
+        "metric": "gradient GB/s through compress+decompress+update",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.grad_dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "matrices": count, "elements": E, "r": r,
+                   "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
+                   "beta": wl.beta if wl.algorithm == 2 else None,
+                   "kappa": wl.kappa if wl.algorithm == 2 else None,
+                   "rule": wl.rule, "grad_sets_in_ring": nsets,
+                   "grad_bytes_per_step": grad_bytes_step},
+        "roofline": roofline,
+        "kernels": kern,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, grad_sets, W, args.cpu_budget_gflop)
+
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, grad_sets, W, budget_gflop):
+    """The fp64 oracle, as it stands, timed on this host over a bounded sample of the same
+    workload: whole matrices taken in order until the flop budget is used (at least one)."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    r = wl.r
+    passes = (wl.tau + 1) if wl.algorithm == 1 else 2
+    if wl.rule == "factored":
+        passes = wl.tau + 1
+    chosen, fl = [], 0.0
+    for l, (n, m) in enumerate(wl.shapes):
+        f = 2.0 * n * m * r * passes / 1e9
+        if chosen and fl + f > budget_gflop:
+            continue
+        chosen.append(l)
+        fl += f
+        if fl >= budget_gflop:
+            break
+
+    def to64(t):
+        return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+    spent = 0.0
+    nbytes = 0
+    gb = 4 if wl.grad_dtype == "f32" else 2
+    for l in chosen:
+        n, m = wl.shapes[l]
+        seed = oracle.derive_seed(99, l, 0)
+        Wl = to64(W[l])
+        if wl.algorithm == 1:
+            C = np.zeros((n, r))
+            for i in range(wl.tau):
+                G = to64(grad_sets[i % len(grad_sets)][l])
+                t0 = time.perf_counter()
+                C = oracle.compress(G, r, seed, state=C)
+                spent += time.perf_counter() - t0
+                nbytes += n * m * gb
+            t0 = time.perf_counter()
+            Gt = oracle.decompress(C, m, seed, alpha=1.0 / wl.tau)
+            if wl.rule == "sgd":
+                oracle.sgd(Wl, Gt, wl.lr)
+            else:
+                ex = wl.extra
+                oracle.factored_update(Wl, Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"],
+                                       ex["clip_d"], wl.lr)
+            spent += time.perf_counter() - t0
+        else:
+            G = to64(grad_sets[0][l])
+            M = np.zeros((n, r))
+            t0 = time.perf_counter()
+            M = oracle.compress(G, r, seed, state=M, a=wl.beta, b=1.0 - wl.beta)
+            Gt = oracle.decompress(M, m, seed)
+            oracle.sgd(Wl, Gt, wl.lr)
+            spent += time.perf_counter() - t0
+            nbytes += n * m * gb
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    omp = os.environ.get("OMP_NUM_THREADS")
+    threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
+    return {
+        "value": nbytes / spent / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": "%d of %d matrices, whole %s, %.1f fp64 GFLOP, %.2f s of oracle calls"
+                  % (len(chosen), len(wl.shapes),
+                     "accumulation cycle" if wl.algorithm == 1 else "optimizer step", fl, spent),
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -141,6 +141,12 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
  * key = global_seed).  Never fails. */
 uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t epoch);
 
+/* The same for `count` consecutive matrix indices at one epoch:
+ * seeds_out[i] = flora_derive_seed(global_seed, first_matrix_id + i, epoch).  seeds_out is a
+ * HOST array of `count` entries; nothing happens if it is NULL or count <= 0. */
+void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int count, uint64_t epoch,
+                        uint64_t* seeds_out);
+
 /* Bytes of private workspace the library would hold for this set of matrices. */
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
 

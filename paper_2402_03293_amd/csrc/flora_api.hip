@@ -346,9 +346,9 @@ bool dtype_ok(int d) { return d == FLORA_F32 || d == FLORA_BF16; }
 
 using namespace flora;
 
-// The seeds ride in the MatDev table (they are part of what is hashed), so a new seed means
-// a table upload of a few KB on the caller's stream; pointers, shapes and work tables are
-// rebuilt only when the shapes change.
+// Seeds travel as kernel arguments (SeedArgs) for compress / decompress / update, so the
+// cached descriptor tables hold only pointers and shapes and a resample uploads nothing.
+// The transfer kernels read both seeds from their (rarely used) table instead.
 static void fill_seed(MatDev& M, const flora_matrix_t& f)
 {
     M.seed_lo = (uint32_t)(f.seed & 0xffffffffu);
@@ -357,86 +357,67 @@ static void fill_seed(MatDev& M, const flora_matrix_t& f)
     M.seedn_hi = (uint32_t)(f.seed_next >> 32);
 }
 
-extern "C" {
-
-int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
-                   float a, float b, void* hip_stream)
+static void fill_seed_args(SeedArgs& sa, const flora_matrix_t* mats, int count, bool use_next)
 {
-    int st = check_common(mats, count, r);
-    if (st != FLORA_OK) return st;
-    if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
-    for (int l = 0; l < count; ++l)
-        if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
-            return FLORA_ERR_INVALID;
-    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
-    if (count == 0) return FLORA_OK;
+    for (int l = 0; l < count; ++l) {
+        const uint64_t sd = use_next ? mats[l].seed_next : mats[l].seed;
+        sa.s[l] = make_uint2((uint32_t)(sd & 0xffffffffu), (uint32_t)(sd >> 32));
+    }
+}
 
-    std::lock_guard<std::mutex> guard(g_lock);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+// ---- one chunk (count <= kMaxSeedArgs) of each entry point; arguments already validated ----
+static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                          float a, float b, bool use_next, hipStream_t s)
+{
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
         MatDev M{};
         M.grad = mats[l].grad; M.state = mats[l].state; M.n = mats[l].n; M.m = mats[l].m;
-        fill_seed(M, mats[l]);
-        M.seedn_lo = M.seedn_hi = 0;
         md[(size_t)l] = M;
     }
+    SeedArgs sa;
+    fill_seed_args(sa, mats, count, use_next);
     const int variant = rank_bf16(r) ? 2 : (grad_dtype == FLORA_BF16 ? 1 : 0);
     Plan* p = nullptr;
-    st = get_plan(kKindCompress, variant, r, md, s, &p);
+    int st = get_plan(kKindCompress, variant, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
-    if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), r, p->mt, a, b, s));
-    else FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), r, variant == 1, a, b, s));
+    if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, s));
+    else FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, s));
     return FLORA_OK;
 }
 
-static int run_decompress(Plan* p, int r, int mode, int out_bf16, DecompressParams dp, hipStream_t s)
+static int run_decompress(Plan* p, const SeedArgs& sa, int r, int mode, int out_bf16, DecompressParams dp,
+                          hipStream_t s)
 {
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
-    if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), r, mode, out_bf16, dp, s));
-    else FLORA_HIP(launch_decompress_f32(dm, di, (int)p->items.size(), r, mode, out_bf16, dp, s));
+    if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, dp, s));
+    else FLORA_HIP(launch_decompress_f32(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, dp, s));
     return FLORA_OK;
 }
 
-int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
-                     flora_dtype_t out_dtype, void* hip_stream)
+static int decompress_chunk(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
+                            flora_dtype_t out_dtype, hipStream_t s)
 {
-    int st = check_common(mats, count, r);
-    if (st != FLORA_OK) return st;
-    if (!dtype_ok((int)out_dtype)) return FLORA_ERR_INVALID;
-    if (count > 0 && !out) return FLORA_ERR_INVALID;
-    for (int l = 0; l < count; ++l)
-        if (!out[l] || !aligned16(out[l]) || out[l] == (void*)mats[l].state) return FLORA_ERR_INVALID;
-    if (count == 0) return FLORA_OK;
-
-    std::lock_guard<std::mutex> guard(g_lock);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
         MatDev M{};
         M.state = mats[l].state; M.out = out[l]; M.n = mats[l].n; M.m = mats[l].m;
-        fill_seed(M, mats[l]);
-        M.seedn_lo = M.seedn_hi = 0;
         md[(size_t)l] = M;
     }
+    SeedArgs sa;
+    fill_seed_args(sa, mats, count, false);
     Plan* p = nullptr;
-    st = get_plan(kKindDecompress, out_dtype == FLORA_BF16 ? 1 : 0, r, md, s, &p);
+    int st = get_plan(kKindDecompress, out_dtype == FLORA_BF16 ? 1 : 0, r, md, s, &p);
     if (st != FLORA_OK) return st;
     DecompressParams dp{alpha, 0.f};
-    return run_decompress(p, r, kModeOut, out_dtype == FLORA_BF16, dp, s);
+    return run_decompress(p, sa, r, kModeOut, out_dtype == FLORA_BF16, dp, s);
 }
 
-int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream)
+static int transfer_chunk(const flora_matrix_t* mats, int count, int r, hipStream_t s)
 {
-    int st = check_common(mats, count, r);
-    if (st != FLORA_OK) return st;
-    if (count == 0) return FLORA_OK;
-
-    std::lock_guard<std::mutex> guard(g_lock);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
         MatDev M{};
@@ -445,12 +426,62 @@ int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* 
         md[(size_t)l] = M;
     }
     Plan* p = nullptr;
-    st = get_plan(kKindTransfer, 0, r, md, s, &p);
+    int st = get_plan(kKindTransfer, 0, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items2);
     FLORA_HIP(launch_transfer_T(dm, count, r, s));
     FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, s));
+    return FLORA_OK;
+}
+
+static int update_chunk(const flora_matrix_t* mats, int count, int r, const flora_update_t* u, bool use_next,
+                        hipStream_t s)
+{
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.weight = static_cast<float*>(mats[l].weight); M.state = mats[l].state;
+        M.n = mats[l].n; M.m = mats[l].m;
+        if (u->rule == FLORA_RULE_FACTORED) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
+        md[(size_t)l] = M;
+    }
+    SeedArgs sa;
+    fill_seed_args(sa, mats, count, use_next);
+    Plan* p = nullptr;
+    const int kind = (u->rule == FLORA_RULE_FACTORED) ? kKindFactored : kKindDecompress;
+    int st = get_plan(kind, 2, r, md, s, &p);
+    if (st != FLORA_OK) return st;
+    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    if (u->rule == FLORA_RULE_SGD) {
+        DecompressParams dp{u->alpha, u->lr * u->alpha};
+        st = run_decompress(p, sa, r, kModeSgd, 0, dp, s);
+        if (st != FLORA_OK) return st;
+    } else {
+        DecompressParams dp{u->alpha, u->lr};
+        st = run_decompress(p, sa, r, kModeStats, 0, dp, s);
+        if (st != FLORA_OK) return st;
+        FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
+        if (u->clip_d > 0.f) {
+            st = run_decompress(p, sa, r, kModeRms, 0, dp, s);
+            if (st != FLORA_OK) return st;
+            FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, s));
+        }
+        st = run_decompress(p, sa, r, kModeFactored, 0, dp, s);
+        if (st != FLORA_OK) return st;
+    }
+    if (u->zero_state_after) FLORA_HIP(launch_zero_state(dm, count, r, s));
+    return FLORA_OK;
+}
+
+// ---- validation of whole calls ----
+static int check_grads(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype)
+{
+    if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
+            return FLORA_ERR_INVALID;
+    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
     return FLORA_OK;
 }
 
@@ -476,43 +507,52 @@ static int check_update(const flora_matrix_t* mats, int count, int r, flora_dtyp
     return FLORA_OK;
 }
 
-static int apply_update_locked(const flora_matrix_t* mats, int count, int r, const flora_update_t* u,
-                               bool use_seed_next, hipStream_t s)
+#define FLORA_FOR_CHUNKS(count, c0, cn) \
+    for (int c0 = 0, cn = 0; c0 < (count) && ((cn = std::min((count) - c0, kMaxSeedArgs)), true); c0 += cn)
+
+extern "C" {
+
+int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                   float a, float b, void* hip_stream)
 {
-    std::vector<MatDev> md((size_t)count);
-    for (int l = 0; l < count; ++l) {
-        MatDev M{};
-        M.weight = static_cast<float*>(mats[l].weight); M.state = mats[l].state;
-        M.n = mats[l].n; M.m = mats[l].m;
-        if (u->rule == FLORA_RULE_FACTORED) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
-        fill_seed(M, mats[l]);
-        if (use_seed_next) { M.seed_lo = M.seedn_lo; M.seed_hi = M.seedn_hi; }
-        M.seedn_lo = M.seedn_hi = 0;
-        md[(size_t)l] = M;
-    }
-    Plan* p = nullptr;
-    const int kind = (u->rule == FLORA_RULE_FACTORED) ? kKindFactored : kKindDecompress;
-    int st = get_plan(kind, 2, r, md, s, &p);
+    int st = check_common(mats, count, r);
     if (st != FLORA_OK) return st;
-    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
-    if (u->rule == FLORA_RULE_SGD) {
-        DecompressParams dp{u->alpha, u->lr * u->alpha};
-        st = run_decompress(p, r, kModeSgd, 0, dp, s);
-        if (st != FLORA_OK) return st;
-    } else {
-        DecompressParams dp{u->alpha, u->lr};
-        st = run_decompress(p, r, kModeStats, 0, dp, s);
-        if (st != FLORA_OK) return st;
-        FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
-        if (u->clip_d > 0.f) {
-            st = run_decompress(p, r, kModeRms, 0, dp, s);
-            if (st != FLORA_OK) return st;
-            FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, s));
-        }
-        st = run_decompress(p, r, kModeFactored, 0, dp, s);
+    st = check_grads(mats, count, r, grad_dtype);
+    if (st != FLORA_OK) return st;
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, false, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
     }
-    if (u->zero_state_after) FLORA_HIP(launch_zero_state(dm, count, r, s));
+    return FLORA_OK;
+}
+
+int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
+                     flora_dtype_t out_dtype, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (!dtype_ok((int)out_dtype)) return FLORA_ERR_INVALID;
+    if (count > 0 && !out) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!out[l] || !aligned16(out[l]) || out[l] == (void*)mats[l].state) return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = decompress_chunk(mats + c0, cn, r, alpha, out + c0, out_dtype, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
+    return FLORA_OK;
+}
+
+int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = transfer_chunk(mats + c0, cn, r, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
     return FLORA_OK;
 }
 
@@ -521,9 +561,12 @@ int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype
 {
     int st = check_update(mats, count, r, weight_dtype, u);
     if (st != FLORA_OK) return st;
-    if (count == 0) return FLORA_OK;
     std::lock_guard<std::mutex> guard(g_lock);
-    return apply_update_locked(mats, count, r, u, false, static_cast<hipStream_t>(hip_stream));
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = update_chunk(mats + c0, cn, r, u, false, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
+    return FLORA_OK;
 }
 
 int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
@@ -532,23 +575,22 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
 {
     int st = check_update(mats, count, r, weight_dtype, u);
     if (st != FLORA_OK) return st;
-    if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
-    for (int l = 0; l < count; ++l)
-        if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
-            return FLORA_ERR_INVALID;
-    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
-    if (count == 0) return FLORA_OK;
-
-    if (do_transfer) {
-        st = flora_momentum_transfer(mats, count, r, hip_stream);
+    st = check_grads(mats, count, r, grad_dtype);
+    if (st != FLORA_OK) return st;
+    std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool next = do_transfer != 0;
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        if (next) {
+            st = transfer_chunk(mats + c0, cn, r, s);
+            if (st != FLORA_OK) return st;
+        }
+        st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, next, s);
+        if (st != FLORA_OK) return st;
+        st = update_chunk(mats + c0, cn, r, u, next, s);
         if (st != FLORA_OK) return st;
     }
-    std::vector<flora_matrix_t> cur(mats, mats + count);
-    if (do_transfer)
-        for (auto& f : cur) f.seed = f.seed_next;
-    st = flora_compress(cur.data(), count, r, grad_dtype, a, b, hip_stream);
-    if (st != FLORA_OK) return st;
-    return flora_apply_update(cur.data(), count, r, weight_dtype, u, hip_stream);
+    return FLORA_OK;
 }
 
 int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out, void* hip_stream)
@@ -566,6 +608,13 @@ uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t ep
                                    kDomainSeed, (uint32_t)(global_seed & 0xffffffffu),
                                    (uint32_t)(global_seed >> 32));
     return (uint64_t)x.w[0] | ((uint64_t)x.w[1] << 32);
+}
+
+void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int count, uint64_t epoch,
+                        uint64_t* seeds_out)
+{
+    if (!seeds_out) return;
+    for (int i = 0; i < count; ++i) seeds_out[i] = flora_derive_seed(global_seed, first_matrix_id + (uint64_t)i, epoch);
 }
 
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)

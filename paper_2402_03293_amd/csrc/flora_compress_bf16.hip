@@ -30,7 +30,7 @@ constexpr int kRS = kCompressBf16Slice;
 template <int MT>
 __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __restrict__ mats,
                                                             const WorkItem* __restrict__ items,
-                                                            int R, float a, float b)
+                                                            const SeedArgs seeds, int R, float a, float b)
 {
     constexpr int NT = kRS / 32;
     __shared__ __attribute__((aligned(16))) uint16_t ldsA[2][kRS][kLda];
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
     const long long n = M.n, m = M.m;
-    const uint32_t seed_lo = M.seed_lo, seed_hi = M.seed_hi;
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
     const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(M.grad);
     float* __restrict__ state = M.state;
 
@@ -162,16 +162,16 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 }  // namespace
 
 // All items of one launch share one MT (rows per workgroup = 128 * MT), chosen by the host.
-hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                                   int mt, float a, float b, hipStream_t s)
+hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
+                                   const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nitems), block(256);
     switch (mt) {
-    case 1: hipLaunchKernelGGL((compress_bf16_kernel<1>), grid, block, 0, s, mats, items, r, a, b); break;
-    case 2: hipLaunchKernelGGL((compress_bf16_kernel<2>), grid, block, 0, s, mats, items, r, a, b); break;
-    case 4: hipLaunchKernelGGL((compress_bf16_kernel<4>), grid, block, 0, s, mats, items, r, a, b); break;
+    case 1: hipLaunchKernelGGL((compress_bf16_kernel<1>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
+    case 2: hipLaunchKernelGGL((compress_bf16_kernel<2>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
+    case 4: hipLaunchKernelGGL((compress_bf16_kernel<4>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

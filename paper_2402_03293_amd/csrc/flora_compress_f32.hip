@@ -52,7 +52,7 @@ __device__ __forceinline__ float4 load4(const uint16_t* rowp, long long col, lon
 template <int R, typename GT, int MT>
 __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restrict__ mats,
                                                            const WorkItem* __restrict__ items,
-                                                           float a, float b)
+                                                           const SeedArgs seeds, float a, float b)
 {
     constexpr int NT = (R + 15) / 16;   // 16-wide column tiles of the state
     constexpr int RP = NT * 16;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restr
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
     const long long n = M.n, m = M.m;
-    const uint32_t seed_lo = M.seed_lo, seed_hi = M.seed_hi;
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
     const GT* __restrict__ G = reinterpret_cast<const GT*>(M.grad);
     float* __restrict__ state = M.state;
 
@@ -177,29 +177,29 @@ __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restr
 }
 
 template <int R, typename GT>
-hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, float a, float b,
-                      hipStream_t s)
+hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                      float a, float b, hipStream_t s)
 {
     constexpr int MT = kCompressF32Rows / 64;
     hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT>), dim3((unsigned)nitems), dim3(256), 0, s,
-                       mats, items, a, b);
+                       mats, items, seeds, a, b);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                               int grad_is_bf16, float a, float b, hipStream_t s)
+hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                               int r, int grad_is_bf16, float a, float b, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (!grad_is_bf16) {
-        if (r == 8) return launch_one<8, float>(mats, items, nitems, a, b, s);
-        if (r == 16) return launch_one<16, float>(mats, items, nitems, a, b, s);
-        if (r == 32) return launch_one<32, float>(mats, items, nitems, a, b, s);
+        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, s);
+        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, s);
+        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, s);
     } else {
-        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, a, b, s);
-        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, a, b, s);
-        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, a, b, s);
+        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, s);
+        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, s);
+        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, s);
     }
     return hipErrorInvalidValue;
 }

@@ -23,7 +23,7 @@ namespace {
 template <int R, int MODE, typename OT>
 __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __restrict__ mats,
                                                               const WorkItem* __restrict__ items,
-                                                              DecompressParams p)
+                                                              const SeedArgs seeds, DecompressParams p)
 {
     constexpr int S = R / 16;          // MFMA steps along the rank axis
     constexpr int LDS_ROW = R + 8;     // padded row (bf16 elements)
@@ -41,12 +41,13 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
     const long long j = (long long)it.col0 + 32 * wave + ln;
     const bool jok = j < m;
     const float cgen = neg2_ln2_over(R);
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
 
     bf16x8 breg[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) {
-        const Quad z0 = normal_quad(M.seed_lo, M.seed_hi, (uint64_t)(jok ? j : 0), (uint32_t)(4 * s + 2 * g), cgen);
-        const Quad z1 = normal_quad(M.seed_lo, M.seed_hi, (uint64_t)(jok ? j : 0), (uint32_t)(4 * s + 2 * g + 1), cgen);
+        const Quad z0 = normal_quad(seed_lo, seed_hi, (uint64_t)(jok ? j : 0), (uint32_t)(4 * s + 2 * g), cgen);
+        const Quad z1 = normal_quad(seed_lo, seed_hi, (uint64_t)(jok ? j : 0), (uint32_t)(4 * s + 2 * g + 1), cgen);
         const uint4 pk = make_uint4(pack_bf16x2(z0.z[0], z0.z[1]), pack_bf16x2(z0.z[2], z0.z[3]),
                                     pack_bf16x2(z1.z[0], z1.z[1]), pack_bf16x2(z1.z[2], z1.z[3]));
         breg[s] = __builtin_bit_cast(bf16x8, pk);
@@ -105,25 +106,25 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
 }
 
 template <int R, typename OT>
-hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, int mode,
-                       DecompressParams p, hipStream_t s)
+hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                       int mode, DecompressParams p, hipStream_t s)
 {
     const dim3 grid((unsigned)nitems), block(256);
     switch (mode) {
     case kModeOut:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeSgd:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeStats:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeRms:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFactored:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;
@@ -132,22 +133,22 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, in
 }
 
 template <int R>
-hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, int mode, int out_is_bf16,
-                    DecompressParams p, hipStream_t s)
+hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int mode,
+                    int out_is_bf16, DecompressParams p, hipStream_t s)
 {
-    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, mode, p, s);
-    return launch_mode<R, float>(mats, items, nitems, mode, p, s);
+    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+    return launch_mode<R, float>(mats, items, nitems, seeds, mode, p, s);
 }
 
 }  // namespace
 
-hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                                  int mode, int out_is_bf16, DecompressParams p, hipStream_t s)
+hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                                 int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
-    if (r == 64) return launch_r<64>(mats, items, nitems, mode, out_is_bf16, p, s);
-    if (r == 128) return launch_r<128>(mats, items, nitems, mode, out_is_bf16, p, s);
-    if (r == 256) return launch_r<256>(mats, items, nitems, mode, out_is_bf16, p, s);
+    if (r == 64) return launch_r<64>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
+    if (r == 128) return launch_r<128>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
+    if (r == 256) return launch_r<256>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
     return hipErrorInvalidValue;
 }
 

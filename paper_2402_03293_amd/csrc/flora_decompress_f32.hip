@@ -24,7 +24,7 @@ namespace {
 template <int R, int MODE, typename OT>
 __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __restrict__ mats,
                                                              const WorkItem* __restrict__ items,
-                                                             DecompressParams p)
+                                                             const SeedArgs seeds, DecompressParams p)
 {
     constexpr int H = R / 2;   // rank entries per lane
     __shared__ float lds_red[4][32];
@@ -39,11 +39,12 @@ __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __res
     const long long j = (long long)it.col0 + 32 * wave + ln;
     const bool jok = j < m;
     const float cgen = neg2_ln2_over(R);
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
 
     float breg[H];
 #pragma unroll
     for (int i = 0; i < R / 8; ++i) {
-        const Quad z = normal_quad(M.seed_lo, M.seed_hi, (uint64_t)(jok ? j : 0),
+        const Quad z = normal_quad(seed_lo, seed_hi, (uint64_t)(jok ? j : 0),
                                    (uint32_t)(g * (R / 8) + i), cgen);
 #pragma unroll
         for (int e = 0; e < 4; ++e) breg[4 * i + e] = z.z[e];
@@ -75,25 +76,25 @@ __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __res
 }
 
 template <int R, typename OT>
-hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, int mode,
-                       DecompressParams p, hipStream_t s)
+hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                       int mode, DecompressParams p, hipStream_t s)
 {
     const dim3 grid((unsigned)nitems), block(256);
     switch (mode) {
     case kModeOut:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeSgd:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeStats:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeRms:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFactored:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;
@@ -102,22 +103,22 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, in
 }
 
 template <int R>
-hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, int mode, int out_is_bf16,
-                    DecompressParams p, hipStream_t s)
+hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int mode,
+                    int out_is_bf16, DecompressParams p, hipStream_t s)
 {
-    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, mode, p, s);
-    return launch_mode<R, float>(mats, items, nitems, mode, p, s);
+    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+    return launch_mode<R, float>(mats, items, nitems, seeds, mode, p, s);
 }
 
 }  // namespace
 
-hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                                 int mode, int out_is_bf16, DecompressParams p, hipStream_t s)
+hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                                 int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
-    if (r == 8) return launch_r<8>(mats, items, nitems, mode, out_is_bf16, p, s);
-    if (r == 16) return launch_r<16>(mats, items, nitems, mode, out_is_bf16, p, s);
-    if (r == 32) return launch_r<32>(mats, items, nitems, mode, out_is_bf16, p, s);
+    if (r == 8) return launch_r<8>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
+    if (r == 16) return launch_r<16>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
+    if (r == 32) return launch_r<32>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
     return hipErrorInvalidValue;
 }
 

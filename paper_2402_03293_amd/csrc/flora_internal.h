@@ -19,9 +19,16 @@ struct MatDev {
     float* itempart;    // [nitems] per-workgroup partial sums of U^2 (workspace)
     float* scal;        // [4]: mean(R), clip scale, spare, spare (workspace)
     long long n, m;
-    uint32_t seed_lo, seed_hi, seedn_lo, seedn_hi;
+    uint32_t seed_lo, seed_hi, seedn_lo, seedn_hi;   // used by the transfer kernels only
     int ncolchunks, nrowblocks;   // decompress tiling of this matrix
     int item0, nitems;            // this matrix's range in the decompress work table
+};
+
+// Seeds of the matrices of one grouped launch, passed by value as a kernel argument:
+// a resample changes nothing in device memory, so there is nothing to upload.
+constexpr int kMaxSeedArgs = 448;
+struct SeedArgs {
+    uint2 s[kMaxSeedArgs];   // (low word, high word) of matrix l's 64-bit seed
 };
 
 // One workgroup's share of a grouped launch.
@@ -70,14 +77,14 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
 // ---- launchers implemented in the kernel translation units ----------------
 hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out, uint32_t* raw_out,
                                  hipStream_t s);
-hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                               int grad_is_bf16, float a, float b, hipStream_t s);
-hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems, int r, int mt,
-                                float a, float b, hipStream_t s);
-hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                                 int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
-hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, int r,
-                                  int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
+hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                               int r, int grad_is_bf16, float a, float b, hipStream_t s);
+hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
+                                   const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s);
+hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                                 int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
+hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
 hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s);
 hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, hipStream_t s);
 hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);

@@ -89,6 +89,8 @@ def lib():
         L.flora_debug_generate.restype = ci
         L.flora_derive_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
         L.flora_derive_seed.restype = ctypes.c_uint64
+        L.flora_derive_seeds.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ci, ctypes.c_uint64, vp]
+        L.flora_derive_seeds.restype = None
         L.flora_workspace_bytes.argtypes = [MP, ci, ci]
         L.flora_workspace_bytes.restype = ctypes.c_size_t
         L.flora_last_device_error.argtypes = []
@@ -105,7 +107,8 @@ def lib():
 
 EXPORTS = [
     "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_apply_update",
-    "flora_fused_step", "flora_debug_generate", "flora_derive_seed", "flora_workspace_bytes",
+    "flora_fused_step", "flora_debug_generate", "flora_derive_seed", "flora_derive_seeds",
+    "flora_workspace_bytes",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
 
@@ -181,6 +184,24 @@ def debug_generate(seed: int, m: int, r: int, A_out=None, raw_out=None, stream=N
 
 def derive_seed(global_seed: int, matrix_id: int, epoch: int) -> int:
     return int(lib().flora_derive_seed(global_seed, matrix_id, epoch))
+
+
+def derive_seeds(global_seed: int, first_matrix_id: int, count: int, epoch: int):
+    """numpy uint64 array of `count` seeds (one C call)."""
+    import numpy as np
+    out = np.empty(count, dtype=np.uint64)
+    lib().flora_derive_seeds(global_seed, first_matrix_id, count, epoch, out.ctypes.data)
+    return out
+
+
+def fields(mats):
+    """A numpy structured view of a flora_matrix_t array: `fields(mats)["seed"][:] = seeds`
+    rewrites one field of every descriptor without a Python loop."""
+    import numpy as np
+    dt = np.dtype([("grad", np.uint64), ("weight", np.uint64), ("state", np.uint64),
+                   ("row_stat", np.uint64), ("col_stat", np.uint64), ("n", np.int64), ("m", np.int64),
+                   ("seed", np.uint64), ("seed_next", np.uint64)])
+    return np.frombuffer(mats, dtype=dt)
 
 
 def workspace_bytes(mats, r: int) -> int:

@@ -311,3 +311,23 @@ def test_error_codes_launch_nothing():
     assert L.flora_compress(bad, 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     sync()
     assert float(S.abs().max()) == 0.0
+
+
+def test_more_matrices_than_one_launch_carries_seeds_for():
+    # seeds ride in the kernel arguments, 448 per launch: 500 matrices take two launches
+    count, n, m, r = 500, 16, 24, 8
+    G = rand((count * n, m), 21)
+    S = torch.zeros((count * n, r), device=DEV)
+    Gs = [G[l * n:(l + 1) * n] for l in range(count)]
+    Ss = [S[l * n:(l + 1) * n] for l in range(count)]
+    seeds = [1000 + l for l in range(count)]
+    flora.compress(flora.matrices([(n, m)] * count, grads=Gs, states=Ss, seeds=seeds), r, flora.F32)
+    sync()
+    for l in (0, 1, 447, 448, 449, 499):
+        assert rel_fro(to64(Ss[l]), oracle.compress(to64(Gs[l]), r, seeds[l])) < TOL_F32
+    out = torch.zeros((count * n, m), device=DEV)
+    outs = [out[l * n:(l + 1) * n] for l in range(count)]
+    flora.decompress(flora.matrices([(n, m)] * count, states=Ss, seeds=seeds), r, 1.0, outs, flora.F32)
+    sync()
+    for l in (0, 447, 448, 499):
+        assert rel_fro(to64(outs[l]), oracle.decompress(to64(Ss[l]), m, seeds[l])) < TOL_F32
