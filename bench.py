@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
     ap.add_argument("--grad-sets", type=int, default=None, help="distinct gradient sets in the ring")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain 1 GiB copy kernel 3 times (profiler yardstick)")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="bracket the launches of every N-th timed step with HIP events")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     return ap.parse_args()
@@ -156,12 +160,20 @@ def main():
             timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
             tstate["t"] += 1
 
+    if args.calibrate_copy:
+        a_ = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        b_ = torch.empty_like(a_)
+        for _ in range(3):
+            flora.debug_copy(a_, b_, 1 << 30, stream)
+        torch.cuda.synchronize()
+        del a_, b_
+
     for _ in range(warmup):
         one_step()
     torch.cuda.synchronize()
-    record["on"] = True
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for i in range(steps):
+        record["on"] = (i % max(1, args.event_every) == 0)
         one_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()

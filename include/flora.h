@@ -22,6 +22,7 @@
  *   - `mats` is a HOST array of `count` descriptors; every pointer inside a
  *     descriptor is a DEVICE pointer owned by the caller, 16-byte aligned.
  *     grad / weight / state of one matrix must not alias.
+ *     1 <= n < 2^31 - 1024 and 1 <= m <= 2^24, else FLORA_ERR_INVALID.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
  *     stream).  All work is enqueued on it; no call synchronises the device
  *     or the stream.
@@ -134,6 +135,11 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
 int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out,
                          void* hip_stream);
 
+/* Measurement hook: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 16;
+ * both DEVICE pointers 16-byte aligned, not overlapping).  Profiler byte counters for the
+ * hot-path kernels are scaled by what they read for this copy of known size. */
+int flora_debug_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 /* Host-side helper: "an independent random seed" (Algorithm 1 initialisation;
  * Algorithm 2 resample branch) as a pure function of a global seed, the
  * matrix's index and its resample count:
@@ -149,6 +155,13 @@ void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int coun
 
 /* Bytes of private workspace the library would hold for this set of matrices. */
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
+
+/* Tuning hook for sweeps: overrides a launch-shape choice the library otherwise makes itself
+ * (value 0 restores the default).  Names: "compress_f32_kgroups" (1, 2, 4: column groups per
+ * workgroup in the fp32 compress kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
+ * in the bf16 compress kernel).  Results never depend on these beyond summation order.
+ * Unknown name or value: FLORA_ERR_INVALID.  Drops the cached descriptor tables. */
+int flora_set_tuning(const char* name, int value);
 
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int flora_last_device_error(void);

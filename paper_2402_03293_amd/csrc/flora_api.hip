@@ -68,6 +68,13 @@ struct Plan {
     size_t off_items = 0, off_items2 = 0, table_bytes = 0;
 };
 
+// Launch-shape knobs, settable through flora_set_tuning (0 = let the library choose).
+struct Tuning {
+    int compress_f32_kgroups = 0;   // column groups per workgroup in the fp32 compress kernel: 1, 2 or 4
+    int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
+};
+Tuning g_tune;
+
 constexpr int kMaxPlans = 96;
 std::vector<Plan*> g_plans;
 uint64_t g_tick = 0;
@@ -106,7 +113,8 @@ void build_compress_bf16_items(Plan& p)
     const int S = p.r / kCompressBf16Slice;
     // largest rows-per-workgroup that still gives the chip at least two workgroups per CU
     int mt = 4;
-    for (; mt > 1; mt >>= 1) {
+    if (g_tune.compress_bf16_mt) mt = g_tune.compress_bf16_mt;
+    else for (; mt > 1; mt >>= 1) {
         long long wgs = 0;
         for (int l = 0; l < p.count; ++l) wgs += (p.host_mats[l].n + 128 * mt - 1) / (128 * mt) * S;
         if (wgs >= 512) break;
@@ -332,7 +340,7 @@ int check_common(const flora_matrix_t* mats, int count, int r)
     if (!rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
     for (int l = 0; l < count; ++l) {
         if (mats[l].n < 1 || mats[l].m < 1) return FLORA_ERR_INVALID;
-        if (mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > 0x7fffffffLL - 1024) return FLORA_ERR_INVALID;
+        if (mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24)) return FLORA_ERR_INVALID;
         if (!mats[l].state || !aligned16(mats[l].state)) return FLORA_ERR_INVALID;
     }
     return FLORA_OK;
@@ -384,7 +392,10 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
     if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, s));
-    else FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, s));
+    else {
+        const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : 4;
+        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, s));
+    }
     return FLORA_OK;
 }
 
@@ -602,6 +613,13 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
     return FLORA_OK;
 }
 
+int flora_debug_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
+{
+    if (!src || !dst || !aligned16(src) || !aligned16(dst) || (bytes % 16) != 0) return FLORA_ERR_INVALID;
+    FLORA_HIP(launch_debug_copy(src, dst, (long long)bytes, static_cast<hipStream_t>(hip_stream)));
+    return FLORA_OK;
+}
+
 uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t epoch)
 {
     const Words4 x = philox4x32_10((uint32_t)matrix_id, (uint32_t)(epoch & 0xffffffffu), (uint32_t)(epoch >> 32),
@@ -634,6 +652,29 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
     }
     return workspace_bytes_for(md, kKindTransfer, r) + workspace_bytes_for(md, kKindFactored, r) +
            sizeof(MatDev) * (size_t)count + sizeof(WorkItem) * items;
+}
+
+int flora_set_tuning(const char* name, int value)
+{
+    if (!name) return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    const bool pow2_124 = value == 0 || value == 1 || value == 2 || value == 4;
+    if (std::strcmp(name, "compress_f32_kgroups") == 0) {
+        if (!pow2_124) return FLORA_ERR_INVALID;
+        g_tune.compress_f32_kgroups = value;
+    } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
+        if (!pow2_124) return FLORA_ERR_INVALID;
+        g_tune.compress_bf16_mt = value;
+    } else {
+        return FLORA_ERR_INVALID;
+    }
+    // cached work tables were built for the old shapes
+    for (Plan* p : g_plans) {
+        if (p->ev_pending) (void)hipEventSynchronize(p->ev);
+        free_plan(p);
+    }
+    g_plans.clear();
+    return FLORA_OK;
 }
 
 int flora_last_device_error(void) { return g_last_hip_error; }

@@ -59,13 +59,13 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
         rowp[mt] = G + row * m;
     }
 
-    auto load_tile = [&](uint4 (&dst)[MT][2], int tile) {
+    auto load_tile = [&](v4u (&dst)[MT][2], int tile) {
         const long long j0 = (long long)tile * kBK + 16 * g;
         if (tile < nfull) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                dst[mt][0] = *reinterpret_cast<const uint4*>(rowp[mt] + j0);
-                dst[mt][1] = *reinterpret_cast<const uint4*>(rowp[mt] + j0 + 8);
+                dst[mt][0] = ldg4(rowp[mt] + j0);
+                dst[mt][1] = ldg4(rowp[mt] + j0 + 8);
             }
         } else {
 #pragma unroll
@@ -74,12 +74,12 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const long long c0 = j0 + 2 * e;
-                    const uint32_t lo = (c0 < m) ? rowp[mt][c0] : 0u;
-                    const uint32_t hi = (c0 + 1 < m) ? rowp[mt][c0 + 1] : 0u;
+                    const uint32_t lo = (c0 < m) ? ldg(rowp[mt] + c0) : 0u;
+                    const uint32_t hi = (c0 + 1 < m) ? ldg(rowp[mt] + c0 + 1) : 0u;
                     w[e] = lo | (hi << 16);
                 }
-                dst[mt][0] = make_uint4(w[0], w[1], w[2], w[3]);
-                dst[mt][1] = make_uint4(w[4], w[5], w[6], w[7]);
+                dst[mt][0] = v4u{w[0], w[1], w[2], w[3]};
+                dst[mt][1] = v4u{w[4], w[5], w[6], w[7]};
             }
         }
     };
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.f;
 
-    uint4 cur[MT][2], nxt[MT][2];
+    v4u cur[MT][2], nxt[MT][2];
     load_tile(cur, 0);
     gen_tile(0, 0);
     __syncthreads();
@@ -139,21 +139,25 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
     }
 
     // D layout of the 32x32 tile: lane holds column lane % 32 and, in register v,
-    // row 8 * (v / 4) + 4 * (lane / 32) + v % 4.
+    // row 8 * (v / 4) + 4 * (lane / 32) + v % 4.  Old values are fetched 16 at a time
+    // (clamped addresses) before the new ones are stored.
     const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int k = it.slice * kRS + nt * 32 + li;
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                long long row = (long long)it.row0 + wave * (MT * 32) + mt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
+                if (row > row_end - 1) row = row_end - 1;
+                old[v] = (a != 0.f) ? ldg(state + row * R + k) : 0.f;
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const long long row = (long long)it.row0 + wave * (MT * 32) + mt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-                if (row < row_end) {
-                    float* p = state + row * R + k;
-                    const float old = (a != 0.f) ? *p : 0.f;
-                    *p = a * old + b * acc[mt][nt][v];
-                }
+                if (row < row_end) stg(state + row * R + k, a * old[v] + b * acc[mt][nt][v]);
             }
         }
     }

@@ -4,10 +4,13 @@
 // a = beta, b = 1 - beta).  G is fp32 or bf16 and is used exactly; products and
 // sums are fp32 (v_mfma_f32_16x16x4_f32).
 //
-// One workgroup (4 waves) owns 64 * MT rows of one matrix and sweeps all m
-// columns in tiles of 64.  For each tile the workgroup regenerates the
-// 64 x r slice of A once into LDS (transposed, [k][j]) and every wave reads
-// its B operands from there, while G streams from HBM straight into the A
+// One workgroup owns 64 * MT rows of one matrix and sweeps all m columns in
+// tiles of 64.  Its 4 * KG waves form KG column groups of 4 waves; group kg
+// takes tiles kg, kg + KG, ... so the chain of dependent tiles per wave is KG
+// times shorter, and the groups' partial sums meet in LDS at the end (fixed
+// order).  For each tile a group regenerates the 64 x r slice of A once into
+// LDS (transposed, [k][j]) and its waves read their B operands from there,
+// while G streams from HBM straight into the A
 // operand registers: lane (row i = lane % 16, group g = lane / 16) loads the
 // four consecutive columns j0 + 16c + 4g .. +3, and MFMA number (c, t) contracts
 // the column set { j0 + 16c + 4g + t : g = 0..3 }.  The order in which columns
@@ -21,42 +24,45 @@ namespace {
 
 constexpr int kBK = 64;         // columns of G per tile
 constexpr int kLda = kBK + 4;   // padded LDS row (floats)
+constexpr int kPF = 4;          // G tiles in flight per wave (register stages)
 
-__device__ __forceinline__ float4 load4(const float* rowp, long long col, long long m, bool fast)
+__device__ __forceinline__ v4f load4(const float* rowp, long long col, long long m, bool fast)
 {
-    if (fast) return *reinterpret_cast<const float4*>(rowp + col);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (col < m) v.x = rowp[col];
-    if (col + 1 < m) v.y = rowp[col + 1];
-    if (col + 2 < m) v.z = rowp[col + 2];
-    if (col + 3 < m) v.w = rowp[col + 3];
+    if (fast) return ldg4(rowp + col);
+    v4f v = {0.f, 0.f, 0.f, 0.f};
+    if (col < m) v.x = ldg(rowp + col);
+    if (col + 1 < m) v.y = ldg(rowp + col + 1);
+    if (col + 2 < m) v.z = ldg(rowp + col + 2);
+    if (col + 3 < m) v.w = ldg(rowp + col + 3);
     return v;
 }
 
-__device__ __forceinline__ float4 load4(const uint16_t* rowp, long long col, long long m, bool fast)
+__device__ __forceinline__ v4f load4(const uint16_t* rowp, long long col, long long m, bool fast)
 {
     uint32_t e0 = 0, e1 = 0, e2 = 0, e3 = 0;
     if (fast) {
-        const uint2 p = *reinterpret_cast<const uint2*>(rowp + col);
+        const v2u p = ldg2(rowp + col);
         e0 = p.x & 0xffffu; e1 = p.x >> 16; e2 = p.y & 0xffffu; e3 = p.y >> 16;
     } else {
-        if (col < m) e0 = rowp[col];
-        if (col + 1 < m) e1 = rowp[col + 1];
-        if (col + 2 < m) e2 = rowp[col + 2];
-        if (col + 3 < m) e3 = rowp[col + 3];
+        if (col < m) e0 = ldg(rowp + col);
+        if (col + 1 < m) e1 = ldg(rowp + col + 1);
+        if (col + 2 < m) e2 = ldg(rowp + col + 2);
+        if (col + 3 < m) e3 = ldg(rowp + col + 3);
     }
-    return make_float4(bf16_bits_to_f32(e0), bf16_bits_to_f32(e1), bf16_bits_to_f32(e2),
-                       bf16_bits_to_f32(e3));
+    v4f v = {bf16_bits_to_f32(e0), bf16_bits_to_f32(e1), bf16_bits_to_f32(e2), bf16_bits_to_f32(e3)};
+    return v;
 }
 
-template <int R, typename GT, int MT>
-__global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restrict__ mats,
-                                                           const WorkItem* __restrict__ items,
-                                                           const SeedArgs seeds, float a, float b)
+template <int R, typename GT, int MT, int KG>
+__global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __restrict__ mats,
+                                                                const WorkItem* __restrict__ items,
+                                                                const SeedArgs seeds, float a, float b)
 {
     constexpr int NT = (R + 15) / 16;   // 16-wide column tiles of the state
     constexpr int RP = NT * 16;
-    __shared__ float ldsA[2][RP][kLda];
+    constexpr int ROWS = 64 * MT;       // rows per workgroup
+    __shared__ float ldsA[KG][2][RP][kLda];
+    __shared__ float ldsRed[(KG > 1) ? KG - 1 : 1][(KG > 1) ? ROWS : 1][RP + 1];
 
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
@@ -66,18 +72,22 @@ __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restr
     float* __restrict__ state = M.state;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
+    const int kg = wave_id >> 2;          // column group of this wave
+    const int tg = tid & 255;             // thread index within the group
+    const int wave = wave_id & 3;         // row slot of this wave within the group
     const int li = lane & 15, g = lane >> 4;
     const float cgen = neg2_ln2_over(R);
     const bool vec_ok = (m % 4) == 0;
     const int ntiles = (int)((m + kBK - 1) / kBK);
-    const int nfull = vec_ok ? (int)(m / kBK) : 0;
+    const int iters = (ntiles + KG - 1) / KG;       // tiles per group (the last may be missing)
 
     if (R < RP) {   // rank 8: the upper half of the 16-wide tile is zero padding
-        for (int idx = tid; idx < 2 * (RP - R) * kLda; idx += 256) {
+        for (int idx = tg; idx < 2 * (RP - R) * kLda; idx += 256) {
             const int bufi = idx / ((RP - R) * kLda);
             const int rem = idx - bufi * (RP - R) * kLda;
-            ldsA[bufi][R + rem / kLda][rem % kLda] = 0.f;
+            ldsA[kg][bufi][R + rem / kLda][rem % kLda] = 0.f;
         }
     }
 
@@ -89,28 +99,56 @@ __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restr
         rowp[mt] = G + row * m;
     }
 
-    auto load_tile = [&](float4 (&dst)[MT][4], int tile) {
-        const bool fast = tile < nfull;
-        const long long j0 = (long long)tile * kBK;
+    // Round i gives tile i * KG + kg to group kg.  When rows are 16-byte aligned (m % 4 == 0)
+    // every round runs in the pipelined loop: loads go through a per-wave buffer resource
+    // that covers exactly the valid rows, a chunk that starts at or beyond column m (ragged
+    // last tile) or belongs to a round past the end (prefetch) is pointed out of range and
+    // comes back as zeros.  Matrices with unaligned rows take the plain guarded loop below.
+    constexpr int ESZ = (int)sizeof(GT);
+    const int fast_rounds = vec_ok ? iters : 0;
+    rsrc_t rs[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+        const long long first = (long long)it.row0 + wave * (MT * 16) + mt * 16;
+        long long valid = n - first;
+        valid = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
+        rs[mt] = make_rsrc(G + (first < n ? first : 0) * m, valid * m * ESZ);
+    }
+    const uint32_t lane_off = ((uint32_t)li * (uint32_t)m + 4u * (uint32_t)g) * ESZ;
+
+    auto load_tile_fast = [&](v4f (&dst)[MT][4], int i) {
+        const int tile = kg + KG * i;
+        const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g;
+        const bool round_ok = i < fast_rounds;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                dst[mt][c] = load4(rowp[mt], j0 + 16 * c + 4 * g, m, fast);
+        for (int c = 0; c < 4; ++c) {
+            const bool ok = round_ok && (col0 + 16u * c < (uint32_t)m);
+            const uint32_t off = ok ? lane_off + ((uint32_t)tile * kBK + 16u * c) * ESZ : kOob;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (ESZ == 4) {
+                    dst[mt][c] = buf_load_f4(rs[mt], off);
+                } else {
+                    const v2u p2 = buf_load_u2(rs[mt], off);
+                    dst[mt][c] = v4f{bf16_bits_to_f32(p2.x & 0xffffu), bf16_bits_to_f32(p2.x >> 16),
+                                     bf16_bits_to_f32(p2.y & 0xffffu), bf16_bits_to_f32(p2.y >> 16)};
+                }
+            }
+        }
     };
 
-    auto gen_tile = [&](int buf, int tile) {
+    auto gen_tile = [&](int buf, int i) {
         constexpr int QT = kBK * (R / 4);
-        const long long j0 = (long long)tile * kBK;
+        const long long j0 = (long long)(kg + KG * i) * kBK;
 #pragma unroll
         for (int idx0 = 0; idx0 < QT; idx0 += 256) {
-            const int idx = idx0 + tid;
+            const int idx = idx0 + tg;
             if (QT % 256 == 0 || idx < QT) {
                 const int jl = idx % kBK;
                 const int q = idx / kBK;
                 const Quad z = normal_quad(seed_lo, seed_hi, (uint64_t)(j0 + jl), (uint32_t)q, cgen);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ldsA[buf][4 * q + i][jl] = z.z[i];
+                for (int e = 0; e < 4; ++e) ldsA[kg][buf][4 * q + e][jl] = z.z[e];
             }
         }
     };
@@ -121,85 +159,147 @@ __global__ __launch_bounds__(256) void compress_f32_kernel(const MatDev* __restr
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    float4 cur[MT][4], nxt[MT][4];
-    load_tile(cur, 0);
-    gen_tile(0, 0);
-    __syncthreads();
-
-    for (int tile = 0; tile < ntiles; ++tile) {
-        const int buf = tile & 1;
-        if (tile + 1 < ntiles) {
-            load_tile(nxt, tile + 1);
-            gen_tile(buf ^ 1, tile + 1);
-        }
+    auto mfma_tile = [&](const v4f (&gt)[MT][4], int buf) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float4 bv[NT];
+            v4f bv[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                bv[nt] = *reinterpret_cast<const float4*>(&ldsA[buf][nt * 16 + li][16 * c + 4 * g]);
+                bv[nt] = *reinterpret_cast<const v4f*>(&ldsA[kg][buf][nt * 16 + li][16 * c + 4 * g]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const float av[4] = {cur[mt][c].x, cur[mt][c].y, cur[mt][c].z, cur[mt][c].w};
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const float bw[4] = {bv[nt].x, bv[nt].y, bv[nt].z, bv[nt].w};
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], bw[t], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(gt[mt][c][t], bv[nt][t],
+                                                                           acc[mt][nt], 0, 0, 0);
+        }
+    };
+
+    // G tiles are fetched kPF - 1 rounds ahead of their use: a wave's progress is then bound
+    // by the matrix cores and the generator, not by one HBM round trip per tile.  The
+    // prefetch is unconditional (out-of-range rounds read zeros for free), which lets the
+    // compiler wait only for the stage it is about to consume.
+    if (fast_rounds > 0) {
+        v4f st[kPF][MT][4];
+#pragma unroll
+        for (int u = 0; u < kPF - 1; ++u) load_tile_fast(st[u], u);
+        gen_tile(0, 0);
+        __syncthreads();
+        for (int base = 0; base < fast_rounds; base += kPF) {
+#pragma unroll
+            for (int u = 0; u < kPF; ++u) {
+                const int i = base + u;
+                if (i < fast_rounds) {
+                    const int buf = i & 1;
+                    load_tile_fast(st[(u + kPF - 1) % kPF], i + kPF - 1);
+                    if (i + 1 < fast_rounds) gen_tile(buf ^ 1, i + 1);
+                    mfma_tile(st[u], buf);
+                    __syncthreads();
                 }
             }
         }
+    }
+    for (int i = fast_rounds; i < iters; ++i) {
+        const int tile = kg + KG * i;
+        const bool active = tile < ntiles;
+        v4f gt[MT][4];
+        if (active) {
+            const long long j0 = (long long)tile * kBK;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) gt[mt][c] = load4(rowp[mt], j0 + 16 * c + 4 * g, m, false);
+            gen_tile(0, i);
+        }
         __syncthreads();
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) cur[mt][c] = nxt[mt][c];
+        if (active) mfma_tile(gt, 0);
+        __syncthreads();
     }
 
     // D layout of the 16x16 tile: lane holds column lane % 16, rows 4 * (lane / 16) + v.
+    // Column groups 1 .. KG-1 hand their partial sums to group 0 through LDS; group 0 adds
+    // them in a fixed order, so the result does not depend on timing.
+    if (KG > 1) {
+        if (kg > 0) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        ldsRed[kg - 1][wave * (MT * 16) + mt * 16 + 4 * g + v][nt * 16 + li] = acc[mt][nt][v];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int k2 = 0; k2 < KG - 1; ++k2)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        acc[mt][nt][v] += ldsRed[k2][wave * (MT * 16) + mt * 16 + 4 * g + v][nt * 16 + li];
+    }
+
+    // All old values are fetched first (clamped addresses), then the new ones are stored.
+    float old[MT][NT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int k = (nt * 16 + li < R) ? nt * 16 + li : R - 1;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                long long row = (long long)it.row0 + wave * (MT * 16) + mt * 16 + 4 * g + v;
+                if (row > n - 1) row = n - 1;
+                old[mt][nt][v] = (a != 0.f) ? ldg(state + row * R + k) : 0.f;
+            }
+        }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int k = nt * 16 + li;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const long long row = (long long)it.row0 + wave * (MT * 16) + mt * 16 + 4 * g + v;
-                if (row < n && k < R) {
-                    float* p = state + row * R + k;
-                    const float old = (a != 0.f) ? *p : 0.f;
-                    *p = a * old + b * acc[mt][nt][v];
-                }
+                if (row < n && k < R) stg(state + row * R + k, a * old[mt][nt][v] + b * acc[mt][nt][v]);
             }
         }
-    }
 }
 
 template <int R, typename GT>
 hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                      float a, float b, hipStream_t s)
+                      float a, float b, int kgroups, hipStream_t s)
 {
     constexpr int MT = kCompressF32Rows / 64;
-    hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT>), dim3((unsigned)nitems), dim3(256), 0, s,
-                       mats, items, seeds, a, b);
+    const dim3 grid((unsigned)nitems);
+    switch (kgroups) {
+    case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1>), grid, dim3(256), 0, s, mats, items, seeds, a, b); break;
+    case 2: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 2>), grid, dim3(512), 0, s, mats, items, seeds, a, b); break;
+    case 4: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 4>), grid, dim3(1024), 0, s, mats, items, seeds, a, b); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, hipStream_t s)
+                               int r, int grad_is_bf16, float a, float b, int kgroups, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (!grad_is_bf16) {
-        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, s);
-        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, s);
-        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, s);
+        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, s);
     } else {
-        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, s);
-        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, s);
-        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, s);
+        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
     }
     return hipErrorInvalidValue;
 }

@@ -31,6 +31,23 @@ __global__ __launch_bounds__(256) void debug_generate_kernel(uint32_t seed_lo, u
     }
 }
 
+// Plain copy of a known size: the yardstick that profiler byte counters are scaled by.
+__global__ __launch_bounds__(256) void debug_copy_kernel(const v4u* __restrict__ src, v4u* __restrict__ dst,
+                                                         long long n16)
+{
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long long)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s)
+{
+    const long long n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    hipLaunchKernelGGL(debug_copy_kernel, dim3(4096), dim3(256), 0, s, static_cast<const v4u*>(src),
+                       static_cast<v4u*>(dst), n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out, uint32_t* raw_out,
                                  hipStream_t s)
 {

@@ -59,16 +59,16 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
 
     // cooperative fetch of a 32 x R block of the state: float4 number f = tid + 256 i
     // covers row f / (R/4), columns 4 (f % (R/4)) .. +3
-    auto fetch = [&](float4 (&dst)[F4], long long rb) {
+    auto fetch = [&](v4f (&dst)[F4], long long rb) {
 #pragma unroll
         for (int i = 0; i < F4; ++i) {
             const int f = tid + 256 * i;
             long long row = rb + f / (R / 4);
             if (row > n - 1) row = n - 1;
-            dst[i] = *reinterpret_cast<const float4*>(state + row * R + 4 * (f % (R / 4)));
+            dst[i] = ldg4(state + row * R + 4 * (f % (R / 4)));
         }
     };
-    auto stash = [&](const float4 (&src)[F4], int buf) {
+    auto stash = [&](const v4f (&src)[F4], int buf) {
 #pragma unroll
         for (int i = 0; i < F4; ++i) {
             const int f = tid + 256 * i;
@@ -77,15 +77,20 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
         }
     };
 
-    float4 stage[F4];
+    v4f stage[F4];
     fetch(stage, it.row0);
+    TilePre<MODE> pre_cur, pre_nxt;
+    epilogue_fetch<MODE>(pre_cur, M, it.row0, row_end, j, jok);
     stash(stage, 0);
     __syncthreads();
 
     int buf = 0;
     for (long long rb = it.row0; rb < row_end; rb += 32) {
         const bool more = rb + 32 < row_end;
-        if (more) fetch(stage, rb + 32);
+        if (more) {
+            fetch(stage, rb + 32);
+            epilogue_fetch<MODE>(pre_nxt, M, rb + 32, row_end, j, jok);
+        }
 
         f32x16 acc;
 #pragma unroll
@@ -96,9 +101,12 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, breg[s], acc, 0, 0, 0);
         }
 
-        epilogue_tile<MODE, OT>(acc, M, it, p, rb, row_end, j, jok, ep, lds_red);
+        epilogue_tile<MODE, OT>(acc, pre_cur, M, it, p, rb, row_end, j, jok, ep, lds_red);
 
-        if (more) stash(stage, buf ^ 1);
+        if (more) {
+            stash(stage, buf ^ 1);
+            pre_cur = pre_nxt;
+        }
         __syncthreads();
         buf ^= 1;
     }

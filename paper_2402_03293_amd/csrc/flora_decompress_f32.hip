@@ -53,24 +53,41 @@ __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __res
     EpilogueLane ep = epilogue_begin<MODE>(M, p, j, jok);
 
     const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
-    for (long long rb = it.row0; rb < row_end; rb += 32) {
+
+    // state rows of a tile: lane = row, this lane's half of the rank axis
+    auto load_state = [&](v4f (&dst)[H / 4], long long rb) {
         long long arow = rb + ln;
         if (arow > n - 1) arow = n - 1;
         const float* sp = state + arow * R + g * H;
-        float areg[H];
 #pragma unroll
-        for (int i = 0; i < H / 4; ++i) {
-            const float4 v = *reinterpret_cast<const float4*>(sp + 4 * i);
-            areg[4 * i] = v.x; areg[4 * i + 1] = v.y; areg[4 * i + 2] = v.z; areg[4 * i + 3] = v.w;
+        for (int i = 0; i < H / 4; ++i) dst[i] = ldg4(sp + 4 * i);
+    };
+
+    // software pipeline: the next tile's state rows and old weights are in flight while the
+    // current tile goes through the matrix cores and is written back
+    v4f a_cur[H / 4], a_nxt[H / 4];
+    TilePre<MODE> pre_cur, pre_nxt;
+    load_state(a_cur, it.row0);
+    epilogue_fetch<MODE>(pre_cur, M, it.row0, row_end, j, jok);
+    for (long long rb = it.row0; rb < row_end; rb += 32) {
+        const bool more = rb + 32 < row_end;
+        if (more) {
+            load_state(a_nxt, rb + 32);
+            epilogue_fetch<MODE>(pre_nxt, M, rb + 32, row_end, j, jok);
         }
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
         for (int s = 0; s < H; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[s], breg[s], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s / 4][s % 4], breg[s], acc, 0, 0, 0);
 
-        epilogue_tile<MODE, OT>(acc, M, it, p, rb, row_end, j, jok, ep, lds_red);
+        epilogue_tile<MODE, OT>(acc, pre_cur, M, it, p, rb, row_end, j, jok, ep, lds_red);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < H / 4; ++i) a_cur[i] = a_nxt[i];
+            pre_cur = pre_nxt;
+        }
     }
     epilogue_end<MODE>(M, it, j, jok, ep, lds_red);
 }

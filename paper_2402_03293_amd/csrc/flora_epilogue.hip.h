@@ -34,20 +34,61 @@ __device__ __forceinline__ EpilogueLane epilogue_begin(const MatDev& M, const De
     e.kfac = 0.f;
     if (MODE == kModeFactored) {
         // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
-        const float meanR = M.scal[0], clip = M.scal[1];
-        e.kfac = jok ? p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(M.col_stat[j]) : 0.f;
+        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
+        e.kfac = jok ? p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + j)) : 0.f;
     }
     if (MODE == kModeRms) {
-        const float meanR = M.scal[0];
-        e.kfac = jok ? p.alpha * p.alpha * meanR / M.col_stat[j] : 0.f;
+        const float meanR = ldg(M.scal);
+        e.kfac = jok ? p.alpha * p.alpha * meanR / ldg(M.col_stat + j) : 0.f;
     }
     return e;
 }
 
+// Values of a tile that the epilogue reads from memory (old weights, row statistics),
+// fetched one tile ahead so that their latency overlaps the previous tile's work.
+template <int MODE>
+struct TilePre {
+    float w[(MODE == kModeSgd || MODE == kModeFactored) ? 16 : 1];
+    float rs[(MODE == kModeRms || MODE == kModeFactored) ? 16 : 1];
+};
+
+// Row of register v of this lane, relative to the tile's first row.
+__device__ __forceinline__ int tile_row(int v, int g) { return 8 * (v / 4) + 4 * g + (v % 4); }
+
+// Addresses inside a tile are a workgroup-uniform base (first row of the tile) plus a 32-bit
+// per-lane element offset row * m + column: 33 m < 2^32 is guaranteed by the host (m <= 2^26).
+template <int MODE>
+__device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev& M, long long rb,
+                                               long long row_end, long long j, bool jok)
+{
+    const int g = (threadIdx.x & 63) >> 5;
+    const uint32_t m32 = (uint32_t)M.m;
+    // Clamped coordinates keep every load in bounds, so all 16 loads of a tile are issued
+    // back to back; only the stores are predicated.
+    const uint32_t jc = jok ? (uint32_t)j : m32 - 1u;
+    const int last = (int)(row_end - 1 - rb);          // last valid row of the tile, relative
+    if (MODE == kModeSgd || MODE == kModeFactored) {
+        const float* tb = M.weight + rb * M.m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+            pre.w[v] = ldg(tb + (rr * m32 + jc));
+        }
+    }
+    if (MODE == kModeRms || MODE == kModeFactored) {
+        const float* rbp = M.row_stat + rb;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+            pre.rs[v] = ldg(rbp + rr);
+        }
+    }
+}
+
 // lds_red: float[4][32] scratch of the workgroup (kModeStats / kModeRms only).
 template <int MODE, typename OT>
-__device__ __forceinline__ void epilogue_tile(const f32x16& acc, const MatDev& M, const WorkItem& it,
-                                              const DecompressParams& p, long long rb,
+__device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<MODE>& pre, const MatDev& M,
+                                              const WorkItem& it, const DecompressParams& p, long long rb,
                                               long long row_end, long long j, bool jok,
                                               EpilogueLane& e, float (*lds_red)[32])
 {
@@ -55,50 +96,58 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const MatDev& M
     const int lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 31, g = lane >> 5;
     const long long n = M.n, m = M.m;
+    const int rows_here = (int)((row_end - rb < 32) ? row_end - rb : 32);
+    const uint32_t m32 = (uint32_t)m, j32 = (uint32_t)j;
     float rowsq[16];
+    if (MODE == kModeOut) {
+        OT* ob = reinterpret_cast<OT*>(M.out) + rb * m;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const long long row = rb + 8 * (v / 4) + 4 * g + (v % 4);
-        const bool ok = jok && row < row_end;
-        if (MODE == kModeOut) {
-            if (ok) {
+        for (int v = 0; v < 16; ++v) {
+            if (jok && tile_row(v, g) < rows_here) {
                 const float val = p.alpha * acc[v];
-                OT* o = reinterpret_cast<OT*>(M.out) + row * m + j;
-                if (sizeof(OT) == 4) *reinterpret_cast<float*>(o) = val;
-                else *reinterpret_cast<uint16_t*>(o) = (uint16_t)f32_to_bf16_bits(val);
-            }
-        } else if (MODE == kModeSgd) {
-            if (ok) {
-                float* w = M.weight + row * m + j;
-                *w = *w - p.coef * acc[v];
-            }
-        } else if (MODE == kModeStats) {
-            const float gt = p.alpha * acc[v];
-            const float q = ok ? gt * gt : 0.f;
-            e.colsum += q;
-            rowsq[v] = q;
-        } else if (MODE == kModeRms) {
-            if (ok) e.colsum += acc[v] * acc[v] * e.kfac / M.row_stat[row];
-        } else if (MODE == kModeFactored) {
-            if (ok) {
-                float* w = M.weight + row * m + j;
-                *w = *w - e.kfac * rsqrtf(M.row_stat[row]) * acc[v];
+                OT* o = ob + ((uint32_t)tile_row(v, g) * m32 + j32);
+                if (sizeof(OT) == 4) stg(reinterpret_cast<float*>(o), val);
+                else stg(reinterpret_cast<uint16_t*>(o), (uint16_t)f32_to_bf16_bits(val));
             }
         }
+    } else if (MODE == kModeSgd) {
+        float* wb = M.weight + rb * m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (jok && tile_row(v, g) < rows_here)
+                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - p.coef * acc[v]);
+    } else if (MODE == kModeStats) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float gt = p.alpha * acc[v];
+            const float q = (jok && tile_row(v, g) < rows_here) ? gt * gt : 0.f;
+            e.colsum += q;
+            rowsq[v] = q;
+        }
+    } else if (MODE == kModeRms) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (jok && tile_row(v, g) < rows_here) e.colsum += acc[v] * acc[v] * e.kfac / pre.rs[v];
+    } else if (MODE == kModeFactored) {
+        float* wb = M.weight + rb * m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (jok && tile_row(v, g) < rows_here)
+                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v]);
     }
     if (MODE == kModeStats) {
         // row sums over this wave's 32 columns, then over the 4 waves in a fixed order
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float s = half_wave_sum(rowsq[v]);
-            if (ln == 0) lds_red[wave][8 * (v / 4) + 4 * g + (v % 4)] = s;
+            if (ln == 0) lds_red[wave][tile_row(v, g)] = s;
         }
         __syncthreads();
         if (tid < 32) {
             const long long row = rb + tid;
             if (row < row_end) {
                 const float s = ((lds_red[0][tid] + lds_red[1][tid]) + lds_red[2][tid]) + lds_red[3][tid];
-                M.rowpart[(long long)it.slice * n + row] = s;
+                stg(M.rowpart + (long long)it.slice * n + row, s);
             }
         }
         __syncthreads();
@@ -114,7 +163,7 @@ __device__ __forceinline__ void epilogue_end(const MatDev& M, const WorkItem& it
     const int g = lane >> 5;
     if (MODE == kModeStats) {
         e.colsum += __shfl_xor(e.colsum, 32);
-        if (g == 0 && jok) M.colpart[(long long)it.rblock * M.m + j] = e.colsum;
+        if (g == 0 && jok) stg(M.colpart + (long long)it.rblock * M.m + j, e.colsum);
     }
     if (MODE == kModeRms) {
         float s = half_wave_sum(e.colsum);

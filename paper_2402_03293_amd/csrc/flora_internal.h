@@ -58,6 +58,61 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 
+// Every pointer in a descriptor is device memory.  Telling the compiler so (address space 1)
+// turns generic flat_load/flat_store into global_load/global_store, which neither touch the
+// LDS counter nor stall on it.
+#define FLORA_GLOBAL __attribute__((address_space(1)))
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float ldg(const float* p) { return *(const FLORA_GLOBAL float*)p; }
+__device__ __forceinline__ v4f ldg4(const float* p) { return *(const FLORA_GLOBAL v4f*)p; }
+__device__ __forceinline__ v2f ldg2(const float* p) { return *(const FLORA_GLOBAL v2f*)p; }
+__device__ __forceinline__ v4u ldg4(const uint16_t* p) { return *(const FLORA_GLOBAL v4u*)p; }
+__device__ __forceinline__ v2u ldg2(const uint16_t* p) { return *(const FLORA_GLOBAL v2u*)p; }
+__device__ __forceinline__ uint32_t ldg(const uint16_t* p) { return *(const FLORA_GLOBAL uint16_t*)p; }
+__device__ __forceinline__ void stg(float* p, float v) { *(FLORA_GLOBAL float*)p = v; }
+__device__ __forceinline__ void stg(uint16_t* p, uint16_t v) { *(FLORA_GLOBAL uint16_t*)p = v; }
+
+// Buffer addressing: a wave-uniform resource (base pointer + size in bytes) plus a 32-bit
+// per-lane byte offset.  The hardware checks the offset against the size: a load beyond it
+// returns zero and a store beyond it is dropped, with no memory traffic.  Sizes are kept
+// below 2^31 so that kOob is out of range for every resource; the host guarantees that by
+// limiting m to 2^24 columns.  Pipelined loops use this to prefetch unconditionally (a
+// prefetch past the end is pointed at kOob) and to mask ragged edges without branches.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOob = 0x80000000u;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, long long bytes)
+{
+    const uint32_t nb = bytes <= 0 ? 0u : (bytes > 0x7fffffffLL ? 0x7fffffffu : (uint32_t)bytes);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)nb, 0x00020000);
+}
+__device__ __forceinline__ v4f buf_load_f4(rsrc_t r, uint32_t off)
+{
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+}
+__device__ __forceinline__ v4u buf_load_u4(rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ v2u buf_load_u2(rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ float buf_load_f(rsrc_t r, uint32_t off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+__device__ __forceinline__ void buf_store_f(rsrc_t r, uint32_t off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, (int)off, 0, 0);
+}
+__device__ __forceinline__ void buf_store_h(rsrc_t r, uint32_t off, uint16_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b16(v, r, (int)off, 0, 0);
+}
+
 // fp32 -> bf16, round to nearest even (finite inputs).
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
@@ -77,8 +132,9 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
 // ---- launchers implemented in the kernel translation units ----------------
 hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out, uint32_t* raw_out,
                                  hipStream_t s);
+hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s);
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, hipStream_t s);
+                               int r, int grad_is_bf16, float a, float b, int kgroups, hipStream_t s);
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
                                    const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s);
 hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,

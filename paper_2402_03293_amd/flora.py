@@ -87,12 +87,16 @@ def lib():
         L.flora_fused_step.restype = ci
         L.flora_debug_generate.argtypes = [ctypes.c_uint64, ctypes.c_int64, ci, vp, vp, vp]
         L.flora_debug_generate.restype = ci
+        L.flora_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.flora_debug_copy.restype = ci
         L.flora_derive_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
         L.flora_derive_seed.restype = ctypes.c_uint64
         L.flora_derive_seeds.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ci, ctypes.c_uint64, vp]
         L.flora_derive_seeds.restype = None
         L.flora_workspace_bytes.argtypes = [MP, ci, ci]
         L.flora_workspace_bytes.restype = ctypes.c_size_t
+        L.flora_set_tuning.argtypes = [ctypes.c_char_p, ci]
+        L.flora_set_tuning.restype = ci
         L.flora_last_device_error.argtypes = []
         L.flora_last_device_error.restype = ci
         L.flora_status_string.argtypes = [ci]
@@ -107,8 +111,8 @@ def lib():
 
 EXPORTS = [
     "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_apply_update",
-    "flora_fused_step", "flora_debug_generate", "flora_derive_seed", "flora_derive_seeds",
-    "flora_workspace_bytes",
+    "flora_fused_step", "flora_debug_generate", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
+    "flora_workspace_bytes", "flora_set_tuning",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
 
@@ -182,6 +186,10 @@ def debug_generate(seed: int, m: int, r: int, A_out=None, raw_out=None, stream=N
            "flora_debug_generate")
 
 
+def debug_copy(src, dst, nbytes: int, stream=None):
+    _check(lib().flora_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "flora_debug_copy")
+
+
 def derive_seed(global_seed: int, matrix_id: int, epoch: int) -> int:
     return int(lib().flora_derive_seed(global_seed, matrix_id, epoch))
 
@@ -215,6 +223,10 @@ def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False) ->
 def factored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
                     zero_state_after: bool = False) -> Update:
     return Update(RULE_FACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after))
+
+
+def set_tuning(name: str, value: int):
+    _check(lib().flora_set_tuning(name.encode(), value), "flora_set_tuning")
 
 
 def shutdown():
