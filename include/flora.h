@@ -158,7 +158,8 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
 
 /* Tuning hook for sweeps: overrides a launch-shape choice the library otherwise makes itself
  * (value 0 restores the default).  Names: "compress_f32_kgroups" (1, 2, 4: column groups per
- * workgroup in the fp32 compress kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
+ * workgroup in the fp32 compress kernel), "compress_f32_mt" (1, 2: rows per workgroup / 64 in
+ * the same kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
  * in the bf16 compress kernel).  Results never depend on these beyond summation order.
  * Unknown name or value: FLORA_ERR_INVALID.  Drops the cached descriptor tables. */
 int flora_set_tuning(const char* name, int value);

@@ -72,6 +72,7 @@ struct Plan {
 struct Tuning {
     int compress_f32_kgroups = 0;   // column groups per workgroup in the fp32 compress kernel: 1, 2 or 4
     int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
+    int compress_f32_mt = 0;        // fp32 compress: rows per workgroup / 64: 1 or 2
 };
 Tuning g_tune;
 
@@ -95,13 +96,15 @@ void build_compress_f32_items(Plan& p)
     for (int i = 0; i < p.count; ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(),
                      [&](int a, int b) { return p.host_mats[a].m > p.host_mats[b].m; });
+    p.mt = g_tune.compress_f32_mt ? g_tune.compress_f32_mt : 1;
+    const int rows_per_wg = 64 * p.mt;
     for (int l : order) {
         const long long n = p.host_mats[l].n;
         int rb = 0;
-        for (long long r0 = 0; r0 < n; r0 += kCompressF32Rows, ++rb) {
+        for (long long r0 = 0; r0 < n; r0 += rows_per_wg, ++rb) {
             WorkItem w{};
             w.mat = l; w.row0 = (int)r0;
-            w.rows = (int)std::min<long long>(kCompressF32Rows, n - r0);
+            w.rows = (int)std::min<long long>(rows_per_wg, n - r0);
             w.rblock = rb;
             p.items.push_back(w);
         }
@@ -393,8 +396,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
     if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, s));
     else {
-        const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : 4;
-        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, s));
+        const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : 2;
+        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, p->mt, s));
     }
     return FLORA_OK;
 }
@@ -662,6 +665,9 @@ int flora_set_tuning(const char* name, int value)
     if (std::strcmp(name, "compress_f32_kgroups") == 0) {
         if (!pow2_124) return FLORA_ERR_INVALID;
         g_tune.compress_f32_kgroups = value;
+    } else if (std::strcmp(name, "compress_f32_mt") == 0) {
+        if (value != 0 && value != 1 && value != 2) return FLORA_ERR_INVALID;
+        g_tune.compress_f32_mt = value;
     } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
         if (!pow2_124) return FLORA_ERR_INVALID;
         g_tune.compress_bf16_mt = value;

@@ -118,11 +118,11 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
 
     auto load_tile_fast = [&](v4f (&dst)[MT][4], int i) {
         const int tile = kg + KG * i;
+        // a round past the end has tile >= ntiles, so its columns fail the same test
         const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g;
-        const bool round_ok = i < fast_rounds;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const bool ok = round_ok && (col0 + 16u * c < (uint32_t)m);
+            const bool ok = col0 + 16u * c < (uint32_t)m;
             const uint32_t off = ok ? lane_off + ((uint32_t)tile * kBK + 16u * c) * ESZ : kOob;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -271,11 +271,10 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         }
 }
 
-template <int R, typename GT>
-hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                      float a, float b, int kgroups, hipStream_t s)
+template <int R, typename GT, int MT>
+hipError_t launch_mt(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                     float a, float b, int kgroups, hipStream_t s)
 {
-    constexpr int MT = kCompressF32Rows / 64;
     const dim3 grid((unsigned)nitems);
     switch (kgroups) {
     case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1>), grid, dim3(256), 0, s, mats, items, seeds, a, b); break;
@@ -286,20 +285,29 @@ hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, con
     return hipGetLastError();
 }
 
+template <int R, typename GT>
+hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                      float a, float b, int kgroups, int mt, hipStream_t s)
+{
+    if (mt == 1) return launch_mt<R, GT, 1>(mats, items, nitems, seeds, a, b, kgroups, s);
+    if (mt == 2) return launch_mt<R, GT, 2>(mats, items, nitems, seeds, a, b, kgroups, s);
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, hipStream_t s)
+                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (!grad_is_bf16) {
-        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, s);
-        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, s);
-        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
     } else {
-        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
-        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
-        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, s);
+        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
     }
     return hipErrorInvalidValue;
 }

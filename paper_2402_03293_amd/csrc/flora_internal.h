@@ -134,7 +134,7 @@ hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out
                                  hipStream_t s);
 hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s);
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, hipStream_t s);
+                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, hipStream_t s);
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
                                    const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s);
 hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
@@ -148,7 +148,6 @@ hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, hipS
 hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s);
 
 // Tiling constants the host needs to build work tables.
-constexpr int kCompressF32Rows = 64;     // rows per workgroup, fp32 matrix-core compress
 constexpr int kCompressBf16Rows = 512;   // rows per workgroup, bf16 matrix-core compress
 constexpr int kCompressBf16Slice = 64;   // rank columns per workgroup, bf16 compress
 constexpr int kDecompressCols = 128;     // columns per workgroup, both decompress kernels
