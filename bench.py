@@ -206,11 +206,19 @@ def main():
         }
     dominant = max((k for k in kern if k != "transfer"), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
     dk = kern[dominant]
+    traffic = None
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")):
+            f = line.split()
+            if len(f) == 4 and f[0] == wl.name and f[1] == dominant:
+                traffic = int(f[2]) + int(f[3])     # profiler-measured bytes per launch (read + written)
+    except OSError:
+        pass
     roofline = {
         "kernel": {"compress": "compress (state <- a*state + b*G*A)",
                    "update": "decompress + update (W <- W - rule(alpha*state*A^T))"}[dominant],
         "bound": "hbm", "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": dk["alg_GBps"] / HBM_PEAK_GBS, "traffic": None,
+        "frac": dk["alg_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
         "bytes_per_launch": alg_bytes[dominant], "avg_launch_ms": dk["avg_ms"],
     }
     if r >= 64:
