@@ -153,14 +153,17 @@ uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t ep
 void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int count, uint64_t epoch,
                         uint64_t* seeds_out);
 
-/* Bytes of private workspace the library would hold for this set of matrices. */
+/* Upper bound on the bytes of private workspace the library would hold for this set of
+ * matrices. */
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
 
 /* Tuning hook for sweeps: overrides a launch-shape choice the library otherwise makes itself
  * (value 0 restores the default).  Names: "compress_f32_kgroups" (1, 2, 4: column groups per
  * workgroup in the fp32 compress kernel), "compress_f32_mt" (1, 2: rows per workgroup / 64 in
  * the same kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
- * in the bf16 compress kernel).  Results never depend on these beyond summation order.
+ * in the bf16 compress kernel; 8: its wide variant, 512 rows, used only when every m is a
+ * multiple of 8), "decompress_rows" (a multiple of 32: rows per workgroup in the
+ * decompress / update kernels).  Results never depend on these beyond summation order.
  * Unknown name or value: FLORA_ERR_INVALID.  Drops the cached descriptor tables. */
 int flora_set_tuning(const char* name, int value);
 

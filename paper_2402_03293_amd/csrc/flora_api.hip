@@ -73,6 +73,7 @@ struct Tuning {
     int compress_f32_kgroups = 0;   // column groups per workgroup in the fp32 compress kernel: 1, 2 or 4
     int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
     int compress_f32_mt = 0;        // fp32 compress: rows per workgroup / 64: 1 or 2
+    int decompress_rows = 0;        // decompress / update: rows per workgroup, a multiple of 32
 };
 Tuning g_tune;
 
@@ -113,21 +114,35 @@ void build_compress_f32_items(Plan& p)
 
 void build_compress_bf16_items(Plan& p)
 {
-    const int S = p.r / kCompressBf16Slice;
-    // largest rows-per-workgroup that still gives the chip at least two workgroups per CU
+    // The wide kernel (512 rows per workgroup, rank slices of 128) regenerates A least often;
+    // it needs 16-byte aligned rows of G and enough row blocks to fill the chip.  Otherwise
+    // the narrow kernel runs with the largest rows-per-workgroup (128 * mt) that still gives
+    // the chip at least two workgroups per compute unit.
+    bool aligned = true;
+    long long wide_wgs = 0;
+    const int wide_slice = (p.r == 64) ? 64 : 128;
+    for (int l = 0; l < p.count; ++l) {
+        aligned = aligned && (p.host_mats[l].m % 8) == 0;
+        wide_wgs += (p.host_mats[l].n + 511) / 512 * (p.r / wide_slice);
+    }
     int mt = 4;
     if (g_tune.compress_bf16_mt) mt = g_tune.compress_bf16_mt;
+    else if (aligned && wide_wgs >= 384) mt = 8;
     else for (; mt > 1; mt >>= 1) {
         long long wgs = 0;
-        for (int l = 0; l < p.count; ++l) wgs += (p.host_mats[l].n + 128 * mt - 1) / (128 * mt) * S;
+        for (int l = 0; l < p.count; ++l)
+            wgs += (p.host_mats[l].n + 128 * mt - 1) / (128 * mt) * (p.r / kCompressBf16Slice);
         if (wgs >= 512) break;
     }
+    if (mt == 8 && !aligned) mt = 4;
     p.mt = mt;
+    const int rows_per_wg = (mt == 8) ? 512 : 128 * mt;
+    const int S = p.r / ((mt == 8) ? wide_slice : kCompressBf16Slice);
     struct Block { int mat, row0, rows, rblock; long long m; };
     std::vector<Block> blocks;
     for (int l = 0; l < p.count; ++l) {
         const long long n = p.host_mats[l].n;
-        const long long nb = (n + 128 * mt - 1) / (128 * mt);
+        const long long nb = (n + rows_per_wg - 1) / rows_per_wg;
         long long per = (n + nb - 1) / nb;
         per = (per + 31) / 32 * 32;
         int rb = 0;
@@ -150,18 +165,39 @@ void build_compress_bf16_items(Plan& p)
     }
 }
 
+// Rows per decompress workgroup.  A workgroup regenerates its 128-column slice of A once
+// and reuses it for every row it owns, so the generator's work is n m r / rows: rows
+// should be as large as the launch allows while the chip still gets several workgroups per
+// compute unit.
+int choose_decompress_rows(const std::vector<MatDev>& mats)
+{
+    if (g_tune.decompress_rows) return g_tune.decompress_rows;
+    long long nmax = 0;
+    for (const MatDev& M : mats) nmax = std::max(nmax, M.n);
+    int rows = kDecompressRows;
+    while (rows < nmax) rows *= 2;
+    for (; rows > kDecompressRows; rows /= 2) {
+        long long wgs = 0;
+        for (const MatDev& M : mats)
+            wgs += ((M.n + rows - 1) / rows) * ((M.m + kDecompressCols - 1) / kDecompressCols);
+        if (wgs >= 2048) break;
+    }
+    return rows;
+}
+
 void build_decompress_items(Plan& p)
 {
+    const int rows_per_wg = choose_decompress_rows(p.host_mats);
     for (int l = 0; l < p.count; ++l) {
         MatDev& M = p.host_mats[l];
-        M.nrowblocks = (int)((M.n + kDecompressRows - 1) / kDecompressRows);
+        M.nrowblocks = (int)((M.n + rows_per_wg - 1) / rows_per_wg);
         M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
         M.item0 = (int)p.items.size();
         for (int rb = 0; rb < M.nrowblocks; ++rb)
             for (int cc = 0; cc < M.ncolchunks; ++cc) {
                 WorkItem w{};
-                w.mat = l; w.row0 = rb * kDecompressRows;
-                w.rows = (int)std::min<long long>(kDecompressRows, M.n - w.row0);
+                w.mat = l; w.row0 = rb * rows_per_wg;
+                w.rows = (int)std::min<long long>(rows_per_wg, M.n - w.row0);
                 w.col0 = cc * kDecompressCols; w.slice = cc; w.rblock = rb;
                 p.items.push_back(w);
             }
@@ -669,8 +705,11 @@ int flora_set_tuning(const char* name, int value)
         if (value != 0 && value != 1 && value != 2) return FLORA_ERR_INVALID;
         g_tune.compress_f32_mt = value;
     } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
-        if (!pow2_124) return FLORA_ERR_INVALID;
+        if (!pow2_124 && value != 8) return FLORA_ERR_INVALID;
         g_tune.compress_bf16_mt = value;
+    } else if (std::strcmp(name, "decompress_rows") == 0) {
+        if (value < 0 || (value % 32) != 0) return FLORA_ERR_INVALID;
+        g_tune.decompress_rows = value;
     } else {
         return FLORA_ERR_INVALID;
     }

@@ -120,9 +120,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
 }
+// Two fp32 -> packed bf16, round to nearest even, one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const v2f v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
 {

@@ -138,6 +138,34 @@ def test_compress_bf16_path(n, m, r):
     assert e < 6e-3          # one bf16-rounded operand: about 2^-9 / sqrt(3)
 
 
+# every launch shape of the bf16 compress kernel, forced through the tuning hook: the narrow
+# kernel (128 / 256 / 512 rows per workgroup) and the wide one (8: 512 rows, rank slices of 128),
+# on shapes with ragged row blocks, a ragged last column tile and odd / even tile counts
+@pytest.mark.parametrize("mt", [1, 2, 4, 8])
+@pytest.mark.parametrize("n,m,r", [(700, 520, 256), (1100, 64, 128), (97, 1160, 64), (513, 200, 256)])
+def test_compress_bf16_every_launch_shape(n, m, r, mt):
+    seed = 2500 + n + m + r
+    G = rand((n, m), seed, torch.bfloat16)
+    S0 = rand((n, r), seed + 1)
+    st = S0.clone()
+    st2 = torch.zeros((n, r), device=DEV)
+    flora.set_tuning("compress_bf16_mt", mt)
+    try:
+        flora.compress(flora.matrices([(n, m)], grads=[G], states=[st], seeds=[seed]), r, flora.BF16, 0.9, 0.1)
+        flora.compress(flora.matrices([(n, m)], grads=[G], states=[st2], seeds=[seed]), r, flora.BF16, 1.0, 1.0)
+        sync()
+    finally:
+        flora.set_tuning("compress_bf16_mt", 0)
+    ref = oracle.compress(to64(G), r, seed, state=to64(S0), a=0.9, b=0.1)
+    ref2 = oracle.compress(to64(G), r, seed)
+    assert rel_fro(to64(st), ref) < TOL_BF16
+    e = rel_fro(to64(st2), ref2)
+    assert e < 6e-3, e
+    # row by row as well: a wrong row block would hide in the Frobenius norm of a large matrix
+    rows = np.linalg.norm(to64(st2) - ref2, axis=1) / np.linalg.norm(ref2, axis=1)
+    assert rows.max() < TOL_BF16, (int(rows.argmax()), float(rows.max()))
+
+
 def test_compress_grouped_many_matrices_and_accumulation():
     shapes = [(96, 128), (64, 300), (130, 64), (32, 32), (200, 72)]
     r, tau = 16, 3
