@@ -165,36 +165,46 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 
 
 // ---------------------------------------------------------------------------
-// Wide variant: 8 waves own 512 rows x (32 NT) rank columns and sweep m in tiles
-// of 64 columns.  It needs rows of G that start on 16-byte boundaries (m % 8 == 0);
-// the kernel above remains for everything else.
+// Wide variant: 8 waves own 512 rows x RS rank columns (RS = 128, or 64 at
+// r = 64) and sweep m in tiles of 64 columns.  It needs rows of G that start on
+// 16-byte boundaries (m % 8 == 0); the kernel above remains for everything else.
 //
-// What bounds this kernel is, in this order, HBM (G is read once from HBM and
-// r / (32 NT) - 1 more times from L2), the vector ALU that regenerates A
-// (evaluations = n m r / 512) and the matrix cores.  To let the three overlap:
-//   * wave w owns rows 64 w .. 64 w + 63 and all 32 NT columns, so G goes from
-//     memory straight into its A-operand registers and is never shared; a lane
-//     (row i = lane % 32, half g = lane / 32) loads the 32 consecutive bf16
-//     G[i, j0 + 32 g .. +31] and MFMA step t contracts the column set
-//     { j0 + 32 g + 8 t + e : g < 2, e < 8 }; per row that is one 128-byte line;
+// What bounds this kernel is, in this order, how fast G reaches the registers
+// (it is read once from HBM and r / RS - 1 more times from L2), the vector ALU
+// that regenerates A (evaluations = n m r / 512) and the matrix cores.
+//   * v_mfma_f32_16x16x32_bf16: its A operand wants lane (row i = lane % 16,
+//     quarter g = lane / 16) to hold 8 consecutive bf16 of row i, so one load
+//     instruction covers 16 rows x 64 contiguous bytes.  The texture path
+//     delivers 16-byte pieces scattered over 32 rows (the 32x32 shapes) at
+//     about 11 bytes per clock per compute unit, 64-byte pieces clearly faster.
+//   * wave w owns rows 64 w .. 64 w + 63 and all RS columns, so G goes from
+//     memory straight into its operand registers and is never shared;
 //   * the registers of a tile are refilled with the tile two steps ahead as soon
 //     as the MFMAs that read them have been issued (two register sets, loop
 //     unrolled by two), so about one and a half tiles are in flight per wave;
-//   * the 64 x (32 NT) slice of A is regenerated once per tile by all 512 threads
-//     into LDS (bf16, transposed, double buffered); waves 0-3 generate first and
-//     multiply second, waves 4-7 the other way round, so that the two waves of
-//     a SIMD keep its vector ALU and its matrix core busy at the same time.
+//   * the 64 x RS slice of A is regenerated once per tile by all 512 threads
+//     into LDS (bf16, transposed, double buffered); waves 0-3 generate while waves
+//     4-7 multiply and the other way round, so that the two waves of a SIMD
+//     keep its vector ALU and its matrix core busy at the same time;
+//   * at the end each wave turns its accumulator tiles into rows through LDS and
+//     updates the state with 16-byte accesses, 512 contiguous bytes per row.
 constexpr int kWBK = 64;             // columns of G per tile
 constexpr int kWLda = kWBK + 8;      // padded LDS row (bf16 elements): 144 bytes
 
-template <int NT>
+template <int CT>   // 16-wide column tiles per wave: RS = 16 CT
 __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* __restrict__ mats,
                                                                  const WorkItem* __restrict__ items,
                                                                  const SeedArgs seeds, int R, float a, float b)
 {
-    constexpr int RS = 32 * NT;      // rank columns of this workgroup
-    constexpr int JG = kWBK / NT;    // threads along j when generating (each takes NT columns j)
-    __shared__ __attribute__((aligned(16))) uint16_t ldsA[2][RS][kWLda];
+    constexpr int RS = 16 * CT;      // rank columns of this workgroup
+    constexpr int NQ = RS / 32;      // quads per thread and tile when generating
+    constexpr int JG = kWBK / NQ;    // threads along j when generating (each takes NQ columns j)
+    constexpr int LDE = RS + 4;      // padded row of the epilogue staging (floats)
+    constexpr int kABytes = 2 * RS * kWLda * 2;
+    constexpr int kEBytes = 8 * 16 * LDE * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kABytes > kEBytes ? kABytes : kEBytes];
+    typedef uint16_t (*lds_a_t)[RS][kWLda];
+    lds_a_t ldsA = reinterpret_cast<lds_a_t>(lds_raw);
 
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
@@ -206,51 +216,44 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int li = lane & 31, g = lane >> 5;
+    const int li = lane & 15, g = lane >> 4;
     const float cgen = neg2_ln2_over(R);
     const int ntiles = (int)((m + kWBK - 1) / kWBK);
     const uint32_t q0 = (uint32_t)(it.slice * (RS / 4));   // first Philox quad of this rank slice
+    const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
+    const long long wave_row0 = (long long)it.row0 + wave * 64;
 
-    // One buffer resource per 32-row tile of this wave, covering exactly its valid rows:
-    // rows past n and (through kOob) columns past m read as zero.
-    rsrc_t rs[2];
+    // One buffer resource for the 64 rows of this wave, covering exactly its valid rows:
+    // rows past the end and (through kOob) columns past m read as zero.
+    long long valid = row_end - wave_row0;
+    valid = valid < 0 ? 0 : (valid > 64 ? 64 : valid);
+    const rsrc_t rs = make_rsrc(G + (wave_row0 < n ? wave_row0 : 0) * m, valid * m * 2);
+    uint32_t lane_off[4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-        const long long first = (long long)it.row0 + wave * 64 + mt * 32;
-        const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
-        long long valid = row_end - first;
-        valid = valid < 0 ? 0 : (valid > 32 ? 32 : valid);
-        rs[mt] = make_rsrc(G + (first < n ? first : 0) * m, valid * m * 2);
-    }
-    const uint32_t lane_off = ((uint32_t)li * (uint32_t)m + 32u * (uint32_t)g) * 2u;
+    for (int rt = 0; rt < 4; ++rt) lane_off[rt] = ((uint32_t)(16 * rt + li) * (uint32_t)m + 8u * (uint32_t)g) * 2u;
 
-    // Byte offset of this lane's chunk t of a tile (kOob when the chunk lies past column m;
-    // m % 8 == 0, so a chunk is all in or all out).
-    auto chunk_off = [&](int tile, int t) -> uint32_t {
-        const uint32_t col = (uint32_t)tile * kWBK + 32u * (uint32_t)g + 8u * (uint32_t)t;
-        return col < (uint32_t)m ? lane_off + ((uint32_t)tile * kWBK + 8u * (uint32_t)t) * 2u : kOob;
-    };
-    auto load_tile = [&](v4u (&dst)[2][4], int tile) {
+    // Chunk (s, g) of a tile holds columns j0 + 32 s + 8 g .. + 7; m % 8 == 0, so a chunk is
+    // all in or all out.  Out-of-range chunks are pointed at kOob and fetch nothing.
+    auto load_half = [&](v4u (&dst)[4][2], int tile, int s) {
+        const uint32_t col = (uint32_t)tile * kWBK + 32u * (uint32_t)s + 8u * (uint32_t)g;
+        const bool ok = col < (uint32_t)m;
+        const uint32_t coff = ((uint32_t)tile * kWBK + 32u * (uint32_t)s) * 2u;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const uint32_t off = chunk_off(tile, t);
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) dst[mt][t] = buf_load_u4(rs[mt], off);
-        }
+        for (int rt = 0; rt < 4; ++rt) dst[rt][s] = buf_load_u4(rs, ok ? lane_off[rt] + coff : kOob);
     };
 
-    // 64 x RS normals per tile = 16 RS quads, NT per thread: thread p takes quad index
-    // q = p / JG for the NT consecutive columns j = NT (p % JG) .. + NT - 1 and writes, for
-    // each of the quad's four rank columns, NT packed bf16 along j.  The quads are evaluated
+    // 64 x RS normals per tile = 16 RS quads, NQ per thread: thread p takes quad index
+    // q = p / JG for the NQ consecutive columns j = NQ (p % JG) .. + NQ - 1 and writes, for
+    // each of the quad's four rank columns, NQ packed bf16 along j.  The quads are evaluated
     // one after the other (a wave gains nothing from interleaving them, and the registers
     // are needed elsewhere); the scheduling barriers keep the compiler from mixing them.
-    const int gen_j = NT * (tid % JG);
+    const int gen_j = NQ * (tid % JG);
     const uint32_t gen_q = (uint32_t)(tid / JG);
     auto gen_tile = [&](int buf, int tile) {
         const uint64_t j = (uint64_t)tile * kWBK + (uint64_t)gen_j;
-        uint32_t pk[NT / 2][4];
+        uint32_t pk[NQ / 2][4];
 #pragma unroll
-        for (int e = 0; e < NT; e += 2) {
+        for (int e = 0; e < NQ; e += 2) {
             const Quad z0 = normal_quad(seed_lo, seed_hi, j + e, q0 + gen_q, cgen);
             __builtin_amdgcn_sched_barrier(0);
             const Quad z1 = normal_quad(seed_lo, seed_hi, j + e + 1, q0 + gen_q, cgen);
@@ -261,41 +264,38 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             uint16_t* dst = &ldsA[buf][4 * gen_q + i][gen_j];
-            if (NT == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0][i], pk[NT / 2 - 1][i]);
+            if (NQ == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0][i], pk[NQ / 2 - 1][i]);
             else *reinterpret_cast<uint32_t*>(dst) = pk[0][i];
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    f32x16 acc[2][NT];
+    f32x4 acc[4][CT];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.f;
+        for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // The tile in `gt` / LDS buffer `buf` goes through the matrix cores; as soon as the MFMAs
-    // of chunk t are issued, the registers of chunk t are refilled with the tile two steps
-    // ahead (past the end every chunk is out of range and nothing is fetched).
-    auto mfma_tile = [&](v4u (&gt)[2][4], int buf, int tile) {
+    // The tile in `gt` / LDS buffer `buf` goes through the matrix cores, one half (32
+    // columns) at a time; the B operand of column tile ct + 1 is fetched from LDS while tile
+    // ct multiplies.  As soon as the MFMAs of a half are issued its registers are refilled
+    // with the tile two steps ahead.
+    auto mfma_tile = [&](v4u (&gt)[4][2], int buf, int tile) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            bf16x8 bv[NT];
+        for (int s = 0; s < 2; ++s) {
+            bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsA[buf][li][32 * s + 8 * g]);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                bv[nt] = *reinterpret_cast<const bf16x8*>(&ldsA[buf][nt * 32 + li][32 * g + 8 * t]);
+            for (int ct = 0; ct < CT; ++ct) {
+                bf16x8 bn = bv;
+                if (ct + 1 < CT) bn = *reinterpret_cast<const bf16x8*>(&ldsA[buf][16 * (ct + 1) + li][32 * s + 8 * g]);
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const bf16x8 av = __builtin_bit_cast(bf16x8, gt[mt][t]);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv[nt], acc[mt][nt], 0, 0, 0);
+                for (int rt = 0; rt < 4; ++rt)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, gt[rt][s]), bv,
+                                                                          acc[rt][ct], 0, 0, 0);
+                bv = bn;
             }
             __builtin_amdgcn_sched_barrier(0);
-            const uint32_t off = chunk_off(tile + 2, t);
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) gt[mt][t] = buf_load_u4(rs[mt], off);
+            load_half(gt, tile + 2, s);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -312,46 +312,61 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         if (mine && tile < ntiles) gen_tile(buf, tile);
     };
 
-    v4u gx[2][4], gy[2][4];
-    load_tile(gx, 0);
-    load_tile(gy, 1);
+    v4u gx[4][2], gy[4][2];
+    load_half(gx, 0, 0);
+    load_half(gx, 0, 1);
+    load_half(gy, 1, 0);
+    load_half(gy, 1, 1);
     gen_tile(0, 0);
     gen_if(early, 1, 1);
     __syncthreads();
-    for (int tile = 0;; tile += 2) {
+    for (int tile = 0; tile < ntiles; tile += 2) {
         mfma_tile(gx, 0, tile);
         gen_if(!early, 1, tile + 1);
         __syncthreads();
         gen_if(early, 0, tile + 2);
-        if (tile + 1 >= ntiles) break;
-        mfma_tile(gy, 1, tile + 1);
+        if (tile + 1 < ntiles) mfma_tile(gy, 1, tile + 1);     // uniform over the workgroup
         gen_if(!early, 0, tile + 2);
         __syncthreads();
         gen_if(early, 1, tile + 3);
-        if (tile + 2 >= ntiles) break;
     }
+    __syncthreads();   // the staging area below overlays the A buffers
 
-    // D layout of a 32x32 tile: lane holds column lane % 32 and, in register v,
-    // row 8 * (v / 4) + 4 * (lane / 32) + v % 4.
-    const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
+    // Epilogue.  D layout of a 16x16 tile: lane holds column lane % 16 and, in register v,
+    // row 4 * (lane / 16) + v.  Each wave writes one 16 x RS block of rows at a time to its own
+    // staging area and reads it back so that a lane holds four consecutive rank columns of
+    // one row: the state is then read and written 16 bytes per lane, RS * 4 contiguous
+    // bytes per row.  The state's buffer resource ends at the last valid row of this wave.
+    float* stage = reinterpret_cast<float*>(lds_raw) + wave * (16 * LDE);
+    const rsrc_t st_rs = make_rsrc(state + (wave_row0 < n ? wave_row0 : 0) * R, valid * R * 4);
+    constexpr int LPR = RS / 4;           // lanes per row when reading back
+    constexpr int RPI = 64 / LPR;         // rows per instruction
+    constexpr int NP = 16 / RPI;          // passes per block of 16 rows
+    const int erow = lane / LPR, echunk = lane % LPR;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int rt = 0; rt < 4; ++rt) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int k = it.slice * RS + nt * 32 + li;
-            float old[16];
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                long long row = (long long)it.row0 + wave * 64 + mt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-                if (row > row_end - 1) row = row_end - 1;
-                old[v] = (a != 0.f) ? ldg(state + row * R + k) : 0.f;
-            }
+            for (int v = 0; v < 4; ++v) stage[(4 * g + v) * LDE + 16 * ct + li] = acc[rt][ct][v];
+        // a wave's own LDS writes are visible to its own later reads once they have completed
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        v4f oldv[NP];
+        uint32_t goff[NP];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const long long row = (long long)it.row0 + wave * 64 + mt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-                if (row < row_end) stg(state + row * R + k, a * old[v] + b * acc[mt][nt][v]);
-            }
+        for (int p = 0; p < NP; ++p) {
+            const int row = 16 * rt + erow + RPI * p;     // row within the wave's 64
+            goff[p] = ((uint32_t)row * (uint32_t)R + (uint32_t)(it.slice * RS + 4 * echunk)) * 4u;
+            oldv[p] = (a != 0.f) ? buf_load_f4(st_rs, goff[p]) : v4f{0.f, 0.f, 0.f, 0.f};
         }
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const v4f nv = *reinterpret_cast<const v4f*>(&stage[(erow + RPI * p) * LDE + 4 * echunk]);
+            const v4f res = {a * oldv[p].x + b * nv.x, a * oldv[p].y + b * nv.y, a * oldv[p].z + b * nv.z,
+                             a * oldv[p].w + b * nv.w};
+            buf_store_f4(st_rs, goff[p], res);
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // reads done before the next block overwrites the area
     }
 }
 
@@ -365,8 +380,8 @@ hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, in
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
     if (mt == 8) {   // wide kernel: 512 rows per workgroup, rank slices of 128 (64 at r = 64)
         const dim3 grid((unsigned)nitems), block(512);
-        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<2>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        else hipLaunchKernelGGL((compress_bf16_wide_kernel<4>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8>), grid, block, 0, s, mats, items, seeds, r, a, b);
         return hipGetLastError();
     }
     const dim3 grid((unsigned)nitems), block(256);

@@ -108,6 +108,10 @@ __device__ __forceinline__ void buf_store_f(rsrc_t r, uint32_t off, float v)
 {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, (int)off, 0, 0);
 }
+__device__ __forceinline__ void buf_store_f4(rsrc_t r, uint32_t off, v4f v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)off, 0, 0);
+}
 __device__ __forceinline__ void buf_store_h(rsrc_t r, uint32_t off, uint16_t v)
 {
     __builtin_amdgcn_raw_buffer_store_b16(v, r, (int)off, 0, 0);
