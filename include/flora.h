@@ -163,7 +163,9 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
  * the same kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
  * in the bf16 compress kernel; 8: its wide variant, 512 rows, used only when every m is a
  * multiple of 8), "decompress_rows" (a multiple of 32: rows per workgroup in the
- * decompress / update kernels).  Results never depend on these beyond summation order.
+ * decompress / update kernels), "decompress_vec" (1: always the 4-byte-per-lane kernel at
+ * ranks >= 64, 2: the 16-byte-per-lane kernel whenever every m is a multiple of 4, which is
+ * also the default).  Results never depend on these beyond summation order.
  * Unknown name or value: FLORA_ERR_INVALID.  Drops the cached descriptor tables. */
 int flora_set_tuning(const char* name, int value);
 

@@ -55,6 +55,7 @@ struct Plan {
     std::vector<WorkItem> items;        // main work table
     std::vector<WorkItem> items2;       // transfer: state <- state T table
     int mt = 1;                         // bf16 compress: rows per workgroup = 128 * mt
+    int vec = 0;                        // decompress: the 16-byte-per-lane bf16 kernel (256-column workgroups)
     void* d_table = nullptr;            // MatDev[count] + items + items2
     size_t table_cap = 0;
     void* d_work = nullptr;             // T / statistic partials
@@ -74,6 +75,7 @@ struct Tuning {
     int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
     int compress_f32_mt = 0;        // fp32 compress: rows per workgroup / 64: 1 or 2
     int decompress_rows = 0;        // decompress / update: rows per workgroup, a multiple of 32
+    int decompress_vec = -1;        // bf16 decompress: -1 choose, 0 scalar kernel, 1 vector kernel when aligned
 };
 Tuning g_tune;
 
@@ -165,21 +167,19 @@ void build_compress_bf16_items(Plan& p)
     }
 }
 
-// Rows per decompress workgroup.  A workgroup regenerates its 128-column slice of A once
-// and reuses it for every row it owns, so the generator's work is n m r / rows: rows
-// should be as large as the launch allows while the chip still gets several workgroups per
-// compute unit.
-int choose_decompress_rows(const std::vector<MatDev>& mats)
+// Rows per decompress workgroup (an upper limit; each matrix splits its rows evenly below it).
+// A workgroup regenerates its slice of A once and reuses it for every row it owns, so the
+// generator's work is n m r / rows: 1024 rows make it a few percent of the kernel.  More
+// would only make workgroups long and unequal (the last ones to start then run alone);
+// fewer are chosen when the launch would otherwise not fill the chip.
+int choose_decompress_rows(const std::vector<MatDev>& mats, int cols)
 {
     if (g_tune.decompress_rows) return g_tune.decompress_rows;
-    long long nmax = 0;
-    for (const MatDev& M : mats) nmax = std::max(nmax, M.n);
-    int rows = kDecompressRows;
-    while (rows < nmax) rows *= 2;
+    int rows = 1024;
     for (; rows > kDecompressRows; rows /= 2) {
         long long wgs = 0;
         for (const MatDev& M : mats)
-            wgs += ((M.n + rows - 1) / rows) * ((M.m + kDecompressCols - 1) / kDecompressCols);
+            wgs += ((M.n + rows - 1) / rows) * ((M.m + cols - 1) / cols);
         if (wgs >= 2048) break;
     }
     return rows;
@@ -187,18 +187,28 @@ int choose_decompress_rows(const std::vector<MatDev>& mats)
 
 void build_decompress_items(Plan& p)
 {
-    const int rows_per_wg = choose_decompress_rows(p.host_mats);
+    // the 16-byte-per-lane kernel needs rows of W that start on 16-byte boundaries and 32-bit
+    // lane offsets (32 m * 4 bytes below 2^31)
+    int vec = rank_bf16(p.r) && (g_tune.decompress_vec != 0);
+    for (const MatDev& M : p.host_mats) vec = vec && (M.m % 4) == 0 && M.m <= (1LL << 23);
+    p.vec = vec;
+    const int cols = vec ? kDecompressColsVec : kDecompressCols;
+    const int rows_per_wg = choose_decompress_rows(p.host_mats, cols);
     for (int l = 0; l < p.count; ++l) {
         MatDev& M = p.host_mats[l];
         M.nrowblocks = (int)((M.n + rows_per_wg - 1) / rows_per_wg);
-        M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
+        M.ncolchunks = (int)((M.m + cols - 1) / cols);
         M.item0 = (int)p.items.size();
+        // equal row blocks, a multiple of 32 rows each
+        long long per = (M.n + M.nrowblocks - 1) / M.nrowblocks;
+        per = (per + 31) / 32 * 32;
+        M.nrowblocks = (int)((M.n + per - 1) / per);
         for (int rb = 0; rb < M.nrowblocks; ++rb)
             for (int cc = 0; cc < M.ncolchunks; ++cc) {
                 WorkItem w{};
-                w.mat = l; w.row0 = rb * rows_per_wg;
-                w.rows = (int)std::min<long long>(rows_per_wg, M.n - w.row0);
-                w.col0 = cc * kDecompressCols; w.slice = cc; w.rblock = rb;
+                w.mat = l; w.row0 = (int)(rb * per);
+                w.rows = (int)std::min<long long>(per, M.n - w.row0);
+                w.col0 = cc * cols; w.slice = cc; w.rblock = rb;
                 p.items.push_back(w);
             }
         M.nitems = (int)p.items.size() - M.item0;
@@ -443,7 +453,7 @@ static int run_decompress(Plan* p, const SeedArgs& sa, int r, int mode, int out_
 {
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
-    if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, dp, s));
+    if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, p->vec, dp, s));
     else FLORA_HIP(launch_decompress_f32(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, dp, s));
     return FLORA_OK;
 }
@@ -707,6 +717,9 @@ int flora_set_tuning(const char* name, int value)
     } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
         if (!pow2_124 && value != 8) return FLORA_ERR_INVALID;
         g_tune.compress_bf16_mt = value;
+    } else if (std::strcmp(name, "decompress_vec") == 0) {
+        if (value < 0 || value > 2) return FLORA_ERR_INVALID;
+        g_tune.decompress_vec = value == 0 ? -1 : value - 1;     // 0 default, 1 scalar, 2 vector
     } else if (std::strcmp(name, "decompress_rows") == 0) {
         if (value < 0 || (value % 32) != 0) return FLORA_ERR_INVALID;
         g_tune.decompress_rows = value;

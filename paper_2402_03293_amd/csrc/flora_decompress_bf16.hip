@@ -113,6 +113,335 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
     epilogue_end<MODE>(M, it, j, jok, ep, lds_red);
 }
 
+// ---------------------------------------------------------------------------
+// Vector variant for rows of W that start on 16-byte boundaries (m % 4 == 0):
+// the product is taken transposed, Gt^T = A state^T, on
+// v_mfma_f32_16x16x32_bf16, so that the accumulator of a 16 x 16 tile holds, per
+// lane, four consecutive columns of one row of W (lane % 16 = row, lane / 16 =
+// group of four columns).  W is then read and written 16 bytes per lane,
+// 16 rows x 64 contiguous bytes per instruction, instead of 4 bytes per lane.
+//
+// One workgroup (8 waves) owns 256 columns and a block of rows; a wave owns 32
+// columns (two 16-wide tiles).  (The state block a workgroup fetches per 32 rows
+// is r * 128 bytes whatever its width; at r = 256 that is as much as the old and
+// new weights of 128 columns together, so the wider the workgroup the smaller
+// the state's share of the load path.)  Lane (column jj = lane % 16, quarter g = lane / 16)
+// regenerates A[j, 32 s + 8 g .. +7] for every step s < r / 32, both tiles, once
+// (r / 8 Philox calls), straight into the A operand registers, and keeps them
+// while the workgroup walks down the rows 32 at a time.  The 32 x r block of the
+// state is converted to bf16 once per workgroup and shared through LDS (double
+// buffered).  The old weights of the next two blocks are in flight while the
+// current block multiplies.
+template <int MODE>
+struct VecPre {
+    v4f w[(MODE == kModeSgd || MODE == kModeFactored) ? 4 : 1];   // [i-tile * 2 + j-tile]
+    float rs[(MODE == kModeRms || MODE == kModeFactored) ? 2 : 1]; // row statistic of this lane's two rows
+};
+
+template <int R, int MODE, typename OT>
+__global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* __restrict__ mats,
+                                                                  const WorkItem* __restrict__ items,
+                                                                  const SeedArgs seeds, DecompressParams p)
+{
+    constexpr int S = R / 32;          // MFMA steps along the rank axis
+    constexpr int LDS_ROW = R + 8;     // padded row (bf16 elements)
+    constexpr int F4 = R / 64;         // float4 loads per thread for one 32 x R block
+    constexpr bool kUsesW = (MODE == kModeSgd || MODE == kModeFactored);
+    constexpr bool kUsesRs = (MODE == kModeRms || MODE == kModeFactored);
+    __shared__ __attribute__((aligned(16))) uint16_t ldsS[2][32][LDS_ROW];
+    __shared__ float lds_row[2][8][32];   // kModeStats: per-wave row sums of a block, double buffered
+    __shared__ float lds_fin[8];
+
+    const WorkItem it = items[blockIdx.x];
+    const MatDev& M = mats[it.mat];
+    const long long n = M.n, m = M.m;
+    const float* __restrict__ state = M.state;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, g = lane >> 4;
+    const float cgen = neg2_ln2_over(R);
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
+    const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
+
+    // A operand: this lane's column of each tile, r / 4 entries per tile
+    bf16x8 areg[2][S];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+        long long j = (long long)it.col0 + 32 * wave + 16 * jt + li;
+        if (j > m - 1) j = m - 1;      // clamped: columns past m are never stored
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const Quad z0 = normal_quad(seed_lo, seed_hi, (uint64_t)j, (uint32_t)(8 * s + 2 * g), cgen);
+            const Quad z1 = normal_quad(seed_lo, seed_hi, (uint64_t)j, (uint32_t)(8 * s + 2 * g + 1), cgen);
+            const uint4 pk = make_uint4(pack_bf16x2(z0.z[0], z0.z[1]), pack_bf16x2(z0.z[2], z0.z[3]),
+                                        pack_bf16x2(z1.z[0], z1.z[1]), pack_bf16x2(z1.z[2], z1.z[3]));
+            areg[jt][s] = __builtin_bit_cast(bf16x8, pk);
+        }
+    }
+
+    // Output coordinates of this lane: row = block row + 16 * i-tile + li, columns
+    // c0[jt] .. c0[jt] + 3; m % 4 == 0, so the four columns are all in or all out.
+    uint32_t c0[2];
+    bool cok[2];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+        c0[jt] = (uint32_t)it.col0 + 32u * wave + 16u * jt + 4u * g;
+        cok[jt] = c0[jt] < (uint32_t)m;
+    }
+
+    // per-column factors (kModeRms / kModeFactored) and running column sums (kModeStats)
+    float kfac[2][4], colsum[2][4];
+    float total = 0.f;
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            kfac[jt][v] = 0.f;
+            colsum[jt][v] = 0.f;
+        }
+    if (MODE == kModeFactored || MODE == kModeRms) {
+        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (!cok[jt]) continue;
+                const float K = ldg(M.col_stat + c0[jt] + v);
+                // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
+                kfac[jt][v] = (MODE == kModeFactored) ? p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(K)
+                                                      : p.alpha * p.alpha * meanR / K;
+            }
+    }
+
+    // cooperative fetch of a 32 x R block of the state: float4 number f = tid + 512 i
+    // covers row f / (R/4), columns 4 (f % (R/4)) .. +3
+    auto fetch = [&](v4f (&dst)[F4], long long rb) {
+#pragma unroll
+        for (int i = 0; i < F4; ++i) {
+            const int f = tid + 512 * i;
+            long long row = rb + f / (R / 4);
+            if (row > n - 1) row = n - 1;
+            dst[i] = ldg4(state + row * R + 4 * (f % (R / 4)));
+        }
+    };
+    auto stash = [&](const v4f (&src)[F4], int buf) {
+#pragma unroll
+        for (int i = 0; i < F4; ++i) {
+            const int f = tid + 512 * i;
+            const uint2 pk = make_uint2(pack_bf16x2(src[i].x, src[i].y), pack_bf16x2(src[i].z, src[i].w));
+            *reinterpret_cast<uint2*>(&ldsS[buf][f / (R / 4)][4 * (f % (R / 4))]) = pk;
+        }
+    };
+
+    // Old weights / row statistics of the block that starts at row rb.  The buffer resource
+    // covers exactly the block's valid rows: rows past the end read as zero and their
+    // stores are dropped; lane offsets stay below 32 m * 4 <= 2^31.
+    auto wrsrc = [&](long long rb) -> rsrc_t {
+        long long rows = row_end - rb;
+        rows = rows < 0 ? 0 : (rows > 32 ? 32 : rows);
+        const long long base = rb < n ? rb : 0;
+        if (MODE == kModeOut) return make_rsrc(reinterpret_cast<OT*>(M.out) + base * m, rows * m * (long long)sizeof(OT));
+        return make_rsrc(M.weight + base * m, rows * m * 4);
+    };
+    auto woff = [&](int itile, int jt) -> uint32_t {
+        return cok[jt] ? ((uint32_t)(16 * itile + li) * (uint32_t)m + c0[jt]) * (uint32_t)sizeof(OT) : kOob;
+    };
+    auto pre_fetch = [&](VecPre<MODE>& pre, long long rb) {
+        if (kUsesW) {
+            const rsrc_t rw = wrsrc(rb);
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile)
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt) pre.w[itile * 2 + jt] = buf_load_f4(rw, woff(itile, jt));
+        }
+        if (kUsesRs) {
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile) {
+                long long row = rb + 16 * itile + li;
+                if (row > n - 1) row = n - 1;
+                pre.rs[itile] = ldg(M.row_stat + row);
+            }
+        }
+    };
+
+    v4f stage[F4];
+    VecPre<MODE> pre0, pre1, pre2;     // blocks rb, rb + 32, rb + 64
+    fetch(stage, it.row0);
+    pre_fetch(pre0, it.row0);
+    pre_fetch(pre1, (long long)it.row0 + 32);
+    stash(stage, 0);
+    __syncthreads();
+
+    int buf = 0;
+    for (long long rb = it.row0; rb < row_end; rb += 32) {
+        const bool more = rb + 32 < row_end;
+        if (more) fetch(stage, rb + 32);
+        pre_fetch(pre2, rb + 64);      // past the end: empty resource, nothing is fetched
+
+        f32x4 acc[2][2];               // [i-tile][j-tile]
+#pragma unroll
+        for (int itile = 0; itile < 2; ++itile)
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt) acc[itile][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile) {
+                const bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsS[buf][16 * itile + li][32 * s + 8 * g]);
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+                    acc[itile][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[jt][s], bv, acc[itile][jt], 0, 0, 0);
+            }
+        }
+
+        // ---- epilogue on the accumulators: acc[itile][jt][v] = (state A^T)[rb + 16 itile + li, c0[jt] + v]
+        if (MODE == kModeOut) {
+            const rsrc_t rw = wrsrc(rb);
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile)
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt) {
+                    const f32x4 a4 = acc[itile][jt];
+                    if (sizeof(OT) == 4) {
+                        buf_store_f4(rw, woff(itile, jt), v4f{p.alpha * a4[0], p.alpha * a4[1], p.alpha * a4[2], p.alpha * a4[3]});
+                    } else {
+                        const v2u pk = {pack_bf16x2(p.alpha * a4[0], p.alpha * a4[1]), pack_bf16x2(p.alpha * a4[2], p.alpha * a4[3])};
+                        buf_store_u2(rw, woff(itile, jt), pk);
+                    }
+                }
+        } else if (MODE == kModeSgd) {
+            const rsrc_t rw = wrsrc(rb);
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile)
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt) {
+                    const f32x4 a4 = acc[itile][jt];
+                    const v4f w = pre0.w[itile * 2 + jt];
+                    buf_store_f4(rw, woff(itile, jt), v4f{w.x - p.coef * a4[0], w.y - p.coef * a4[1],
+                                                         w.z - p.coef * a4[2], w.w - p.coef * a4[3]});
+                }
+        } else if (MODE == kModeFactored) {
+            const rsrc_t rw = wrsrc(rb);
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile) {
+                const float ri = rsqrtf(pre0.rs[itile]);
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt) {
+                    const f32x4 a4 = acc[itile][jt];
+                    const v4f w = pre0.w[itile * 2 + jt];
+                    buf_store_f4(rw, woff(itile, jt), v4f{w.x - kfac[jt][0] * ri * a4[0], w.y - kfac[jt][1] * ri * a4[1],
+                                                         w.z - kfac[jt][2] * ri * a4[2], w.w - kfac[jt][3] * ri * a4[3]});
+                }
+            }
+        } else if (MODE == kModeStats) {
+            // squares of Gt: column sums stay in registers for the whole sweep; row sums go
+            // over the four column groups of the wave, then over the eight waves through LDS
+            // (fixed order).  Rows past the end hold zeros (their state rows are clamped
+            // copies, so they must be masked) and columns past m are masked as well.
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile) {
+                const bool rok = rb + 16 * itile + li < row_end;
+                float rsum = 0.f;
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float gt = p.alpha * acc[itile][jt][v];
+                        const float q = (rok && cok[jt]) ? gt * gt : 0.f;
+                        colsum[jt][v] += q;
+                        rsum += q;
+                    }
+                rsum += __shfl_xor(rsum, 16);
+                rsum += __shfl_xor(rsum, 32);
+                if (g == 0) lds_row[buf][wave][16 * itile + li] = rsum;
+            }
+        } else if (MODE == kModeRms) {
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile) {
+                const bool rok = rb + 16 * itile + li < row_end;
+                const float rinv = 1.f / pre0.rs[itile];
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (rok) total += acc[itile][jt][v] * acc[itile][jt][v] * kfac[jt][v] * rinv;
+            }
+        }
+
+        if (more) stash(stage, buf ^ 1);
+        pre0 = pre1;
+        pre1 = pre2;
+        __syncthreads();
+        if (MODE == kModeStats && tid < 32) {
+            // the eight waves' row sums of the block just finished (written before the barrier;
+            // the buffer is not written again before the next barrier)
+            const long long row = rb + tid;
+            if (row < row_end)
+                stg(M.rowpart + (long long)it.slice * n + row,
+                    (((lds_row[buf][0][tid] + lds_row[buf][1][tid]) + (lds_row[buf][2][tid] + lds_row[buf][3][tid])) +
+                     ((lds_row[buf][4][tid] + lds_row[buf][5][tid]) + (lds_row[buf][6][tid] + lds_row[buf][7][tid]))));
+        }
+        buf ^= 1;
+    }
+
+    if (MODE == kModeStats) {
+        // column sums over the 16 rows-lanes that share a column group, then one store per column
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float c = colsum[jt][v];
+                c += __shfl_xor(c, 8);
+                c += __shfl_xor(c, 4);
+                c += __shfl_xor(c, 2);
+                c += __shfl_xor(c, 1);
+                if (li == 0 && cok[jt]) stg(M.colpart + (long long)it.rblock * m + c0[jt] + v, c);
+            }
+    }
+    if (MODE == kModeRms) {
+        float t = total;
+        t += __shfl_xor(t, 32);
+        t += __shfl_xor(t, 16);
+        t += __shfl_xor(t, 8);
+        t += __shfl_xor(t, 4);
+        t += __shfl_xor(t, 2);
+        t += __shfl_xor(t, 1);
+        if (lane == 0) lds_fin[wave] = t;
+        __syncthreads();
+        if (tid == 0)
+            M.itempart[(int)blockIdx.x - M.item0] = ((lds_fin[0] + lds_fin[1]) + (lds_fin[2] + lds_fin[3])) +
+                                                    ((lds_fin[4] + lds_fin[5]) + (lds_fin[6] + lds_fin[7]));
+    }
+}
+
+template <int R, typename OT>
+hipError_t launch_mode_vec(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+                           int mode, DecompressParams p, hipStream_t s)
+{
+    const dim3 grid((unsigned)nitems), block(512);
+    switch (mode) {
+    case kModeOut:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeSgd:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeStats:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeRms:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeFactored:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int R, typename OT>
 hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                        int mode, DecompressParams p, hipStream_t s)
@@ -142,21 +471,26 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
 
 template <int R>
 hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int mode,
-                    int out_is_bf16, DecompressParams p, hipStream_t s)
+                    int out_is_bf16, int vec, DecompressParams p, hipStream_t s)
 {
+    if (vec) {
+        if (mode == kModeOut && out_is_bf16) return launch_mode_vec<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+        return launch_mode_vec<R, float>(mats, items, nitems, seeds, mode, p, s);
+    }
     if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
     return launch_mode<R, float>(mats, items, nitems, seeds, mode, p, s);
 }
 
 }  // namespace
 
+// vec: every matrix of the launch has m % 4 == 0 (rows of W / out start on 16-byte boundaries)
 hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                                 int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s)
+                                 int r, int mode, int out_is_bf16, int vec, DecompressParams p, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
-    if (r == 64) return launch_r<64>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
-    if (r == 128) return launch_r<128>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
-    if (r == 256) return launch_r<256>(mats, items, nitems, seeds, mode, out_is_bf16, p, s);
+    if (r == 64) return launch_r<64>(mats, items, nitems, seeds, mode, out_is_bf16, vec, p, s);
+    if (r == 128) return launch_r<128>(mats, items, nitems, seeds, mode, out_is_bf16, vec, p, s);
+    if (r == 256) return launch_r<256>(mats, items, nitems, seeds, mode, out_is_bf16, vec, p, s);
     return hipErrorInvalidValue;
 }
 

@@ -112,6 +112,10 @@ __device__ __forceinline__ void buf_store_f4(rsrc_t r, uint32_t off, v4f v)
 {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)off, 0, 0);
 }
+__device__ __forceinline__ void buf_store_u2(rsrc_t r, uint32_t off, v2u v)
+{
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)off, 0, 0);
+}
 __device__ __forceinline__ void buf_store_h(rsrc_t r, uint32_t off, uint16_t v)
 {
     __builtin_amdgcn_raw_buffer_store_b16(v, r, (int)off, 0, 0);
@@ -147,7 +151,7 @@ hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, in
 hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
 hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
+                                  int r, int mode, int out_is_bf16, int vec, DecompressParams p, hipStream_t s);
 hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s);
 hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, hipStream_t s);
 hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);
@@ -157,7 +161,8 @@ hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s
 // Tiling constants the host needs to build work tables.
 constexpr int kCompressBf16Rows = 512;   // rows per workgroup, bf16 matrix-core compress
 constexpr int kCompressBf16Slice = 64;   // rank columns per workgroup, bf16 compress
-constexpr int kDecompressCols = 128;     // columns per workgroup, both decompress kernels
+constexpr int kDecompressCols = 128;     // columns per workgroup, 4-byte-per-lane decompress kernels
+constexpr int kDecompressColsVec = 256;  // columns per workgroup, 16-byte-per-lane bf16 decompress kernel
 constexpr int kDecompressRows = 256;     // rows per workgroup, both decompress kernels
 constexpr int kApplyTRows = 32;          // rows per workgroup, state <- state T
 

@@ -269,6 +269,50 @@ def test_apply_update_factored(n, m, r, clip_d, beta2):
     assert rel_fro(to64(W) - to64(W0), Wr - to64(W0)) < max(2 * tol, 5e-5)
 
 
+# both bf16 decompress kernels (4-byte and 16-byte accesses per lane), with one and with several
+# row blocks per matrix (which changes how the column statistics are combined), every mode
+@pytest.mark.parametrize("vec", [1, 2])
+@pytest.mark.parametrize("rows", [0, 64])
+@pytest.mark.parametrize("n,m,r", [(300, 520, 64), (257, 264, 256), (200, 1028, 128)])
+def test_bf16_decompress_kernels_every_mode(n, m, r, rows, vec):
+    seed = 7000 + n + r
+    S = rand((n, r), seed)
+    W0 = rand((n, m), seed + 1)
+    R0 = (rand((n,), seed + 2).abs() + 0.1).contiguous()
+    K0 = (rand((m,), seed + 3).abs() + 0.1).contiguous()
+    lr, alpha, eps1, beta2, clip_d = 0.01, 0.5, 1e-30, 0.8, 0.3
+    out32 = torch.full((n, m), float("nan"), device=DEV)
+    out16 = torch.full((n, m), float("nan"), device=DEV, dtype=torch.bfloat16)
+    Ws, Wf, R, K = W0.clone(), W0.clone(), R0.clone(), K0.clone()
+    flora.set_tuning("decompress_vec", vec)
+    flora.set_tuning("decompress_rows", rows)
+    try:
+        flora.decompress(flora.matrices([(n, m)], states=[S], seeds=[seed]), r, alpha, [out32], flora.F32)
+        flora.decompress(flora.matrices([(n, m)], states=[S], seeds=[seed]), r, alpha, [out16], flora.BF16)
+        flora.apply_update(flora.matrices([(n, m)], weights=[Ws], states=[S], seeds=[seed]), r, flora.F32,
+                           flora.sgd_update(lr, alpha))
+        flora.apply_update(flora.matrices([(n, m)], weights=[Wf], states=[S], row_stats=[R], col_stats=[K],
+                                          seeds=[seed]), r, flora.F32,
+                           flora.factored_update(lr, alpha, beta2, eps1, clip_d))
+        sync()
+    finally:
+        flora.set_tuning("decompress_vec", 0)
+        flora.set_tuning("decompress_rows", 0)
+    Gt = oracle.decompress(to64(S), m, seed, alpha=alpha)
+    assert rel_fro(to64(out32), Gt) < TOL_BF16
+    assert rel_fro(to64(out32), Gt) < 6e-3
+    assert rel_fro(to64(out16), Gt) < TOL_BF16
+    # row by row and column by column: a misplaced tile would hide in the norm of the whole
+    d = to64(out32) - Gt
+    assert (np.linalg.norm(d, axis=1) / np.linalg.norm(Gt, axis=1)).max() < TOL_BF16
+    assert (np.linalg.norm(d, axis=0) / np.linalg.norm(Gt, axis=0)).max() < TOL_BF16
+    assert rel_fro(to64(Ws) - to64(W0), oracle.sgd(to64(W0), Gt, lr) - to64(W0)) < TOL_BF16
+    Wr, Rr, Kr = oracle.factored_update(to64(W0), Gt, to64(R0), to64(K0), beta2, eps1, clip_d, lr)
+    assert rel_fro(to64(R), Rr) < 2 * TOL_BF16
+    assert rel_fro(to64(K), Kr) < 2 * TOL_BF16
+    assert rel_fro(to64(Wf) - to64(W0), Wr - to64(W0)) < 2 * TOL_BF16
+
+
 # ---------------------------------------------------- algorithms end to end
 def test_algorithm1_config1_end_to_end():
     wl = workloads.workload(1)
