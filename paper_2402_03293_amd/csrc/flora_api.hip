@@ -56,6 +56,8 @@ struct Plan {
     std::vector<WorkItem> items2;       // transfer: state <- state T table
     int mt = 1;                         // bf16 compress: rows per workgroup = 128 * mt
     int vec = 0;                        // decompress: the 16-byte-per-lane bf16 kernel (256-column workgroups)
+    size_t ws_floats = 0;               // wide bf16 compress: floats of partial products (shared-column mode)
+    size_t ws_counters = 0;             // ... and arrival counters
     void* d_table = nullptr;            // MatDev[count] + items + items2
     size_t table_cap = 0;
     void* d_work = nullptr;             // T / statistic partials
@@ -74,6 +76,7 @@ struct Tuning {
     int compress_f32_kgroups = 0;   // column groups per workgroup in the fp32 compress kernel: 1, 2 or 4
     int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
     int compress_f32_mt = 0;        // fp32 compress: rows per workgroup / 64: 1 or 2
+    int compress_splitk_cols = 0;   // wide bf16 compress: columns per part when a row block's columns are shared
     int decompress_rows = 0;        // decompress / update: rows per workgroup, a multiple of 32
     int decompress_vec = -1;        // bf16 decompress: -1 choose, 0 scalar kernel, 1 vector kernel when aligned
 };
@@ -116,30 +119,56 @@ void build_compress_f32_items(Plan& p)
 
 void build_compress_bf16_items(Plan& p)
 {
-    // The wide kernel (512 rows per workgroup, rank slices of 128) regenerates A least often;
-    // it needs 16-byte aligned rows of G and enough row blocks to fill the chip.  Otherwise
-    // the narrow kernel runs with the largest rows-per-workgroup (128 * mt) that still gives
-    // the chip at least two workgroups per compute unit.
+    // The wide kernel (512 or 256 rows per workgroup, rank slices of 128) regenerates A least
+    // often; it needs 16-byte aligned rows of G.  A launch should give the chip at least one
+    // and a half workgroups per compute unit: if whole row blocks do not, the columns of a row
+    // block are shared between up to a few workgroups (partial products, combined by the last
+    // one to finish), then the row blocks are halved.  Sharing costs nparts * rows * r * 8
+    // bytes of extra traffic per block, so parts stay at 768 columns or more.
+    // Unaligned sets take the narrow kernel with the largest rows-per-workgroup (128 * mt)
+    // that still gives the chip two workgroups per compute unit.
     bool aligned = true;
-    long long wide_wgs = 0;
+    for (int l = 0; l < p.count; ++l) aligned = aligned && (p.host_mats[l].m % 8) == 0;
     const int wide_slice = (p.r == 64) ? 64 : 128;
-    for (int l = 0; l < p.count; ++l) {
-        aligned = aligned && (p.host_mats[l].m % 8) == 0;
-        wide_wgs += (p.host_mats[l].n + 511) / 512 * (p.r / wide_slice);
-    }
+    auto wide_wgs = [&](int rows, long long kc) {
+        long long wgs = 0;
+        for (int l = 0; l < p.count; ++l) {
+            const long long parts = kc > 0 ? (p.host_mats[l].m + kc - 1) / kc : 1;
+            wgs += (p.host_mats[l].n + rows - 1) / rows * (p.r / wide_slice) * parts;
+        }
+        return wgs;
+    };
     int mt = 4;
-    if (g_tune.compress_bf16_mt) mt = g_tune.compress_bf16_mt;
-    else if (aligned && wide_wgs >= 384) mt = 8;
-    else for (; mt > 1; mt >>= 1) {
+    long long kc = 0;       // columns per part (0: whole rows)
+    if (g_tune.compress_bf16_mt) {
+        mt = g_tune.compress_bf16_mt;
+        kc = g_tune.compress_splitk_cols;
+    } else if (aligned) {
+        const int rows_opt[2] = {512, 256};
+        const long long kc_opt[3] = {0, 1536, 768};
+        mt = 16; kc = 768;
+        bool found = false;
+        for (int ri = 0; ri < 2 && !found; ++ri)
+            for (int ki = 0; ki < 3 && !found; ++ki)
+                if (wide_wgs(rows_opt[ri], kc_opt[ki]) >= 384) {
+                    mt = rows_opt[ri] == 512 ? 8 : 16;
+                    kc = kc_opt[ki];
+                    found = true;
+                }
+        if (g_tune.compress_splitk_cols) kc = g_tune.compress_splitk_cols;
+    } else for (; mt > 1; mt >>= 1) {
         long long wgs = 0;
         for (int l = 0; l < p.count; ++l)
             wgs += (p.host_mats[l].n + 128 * mt - 1) / (128 * mt) * (p.r / kCompressBf16Slice);
         if (wgs >= 512) break;
     }
-    if (mt == 8 && !aligned) mt = 4;
+    if (mt >= 8 && !aligned) mt = 4;
+    const bool wide = mt >= 8;
+    if (!wide) kc = 0;
     p.mt = mt;
-    const int rows_per_wg = (mt == 8) ? 512 : 128 * mt;
-    const int S = p.r / ((mt == 8) ? wide_slice : kCompressBf16Slice);
+    const int rows_per_wg = (mt == 8) ? 512 : (mt == 16) ? 256 : 128 * mt;
+    const int slice_w = wide ? wide_slice : kCompressBf16Slice;
+    const int S = p.r / slice_w;
     struct Block { int mat, row0, rows, rblock; long long m; };
     std::vector<Block> blocks;
     for (int l = 0; l < p.count; ++l) {
@@ -155,15 +184,44 @@ void build_compress_bf16_items(Plan& p)
     // Workgroup ids go round-robin over the 8 XCDs.  Give the S rank slices of one
     // row block ids that are equal modulo 8, close together, so that they run on
     // one XCD at about the same time and share its L2 copy of G.
+    p.ws_floats = 0;
+    p.ws_counters = 0;
     for (size_t base = 0; base < blocks.size(); base += 8) {
         const size_t nb = std::min<size_t>(8, blocks.size() - base);
-        for (int s = 0; s < S; ++s)
+        // parts of the blocks of this group of 8 (equal column shares, whole 64-column tiles)
+        int maxparts = 1;
+        int parts[8];
+        long long pcols[8];
+        for (size_t x = 0; x < nb; ++x) {
+            const long long m = blocks[base + x].m;
+            parts[x] = kc > 0 ? (int)((m + kc - 1) / kc) : 1;
+            pcols[x] = ((m + parts[x] - 1) / parts[x] + 63) / 64 * 64;
+            parts[x] = (int)((m + pcols[x] - 1) / pcols[x]);
+            maxparts = std::max(maxparts, parts[x]);
+        }
+        for (int s = 0; s < S; ++s) {
+            long long poff[8];
+            int cidx[8];
             for (size_t x = 0; x < nb; ++x) {
-                const Block& b = blocks[base + x];
-                WorkItem w{};
-                w.mat = b.mat; w.row0 = b.row0; w.rows = b.rows; w.slice = s; w.rblock = b.rblock;
-                p.items.push_back(w);
+                poff[x] = (long long)p.ws_floats;
+                cidx[x] = (int)p.ws_counters;
+                if (parts[x] > 1) {
+                    p.ws_floats += (size_t)parts[x] * rows_per_wg * slice_w;
+                    p.ws_counters += 1;
+                }
             }
+            for (int part = 0; part < maxparts; ++part)
+                for (size_t x = 0; x < nb; ++x) {
+                    if (part >= parts[x]) continue;
+                    const Block& b = blocks[base + x];
+                    WorkItem w{};
+                    w.mat = b.mat; w.row0 = b.row0; w.rows = b.rows; w.slice = s; w.rblock = b.rblock;
+                    w.col0 = (int)(part * pcols[x]);
+                    w.col1 = (int)std::min<long long>(b.m, (part + 1) * pcols[x]);
+                    w.part = part; w.nparts = parts[x]; w.poff = poff[x]; w.cidx = cidx[x];
+                    p.items.push_back(w);
+                }
+        }
     }
 }
 
@@ -338,10 +396,16 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
         p->off_items = round_up(sizeof(MatDev) * (size_t)count, 256);
         p->off_items2 = p->off_items + round_up(sizeof(WorkItem) * p->items.size(), 256);
         p->table_bytes = p->off_items2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
-        const size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
+        size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
+        if (kind == kKindCompress) wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
+        if (p->d_work) { (void)hipFree(p->d_work); p->d_work = nullptr; }
         if (wbytes > 0) {
             FLORA_HIP(hipMalloc(&p->d_work, wbytes));
             p->work_cap = wbytes;
+            // arrival counters start at zero (the kernel leaves them at zero again)
+            if (kind == kKindCompress && p->ws_counters > 0)
+                FLORA_HIP(hipMemsetAsync(static_cast<char*>(p->d_work) + round_up(p->ws_floats * 4, 256), 0,
+                                         p->ws_counters * 4, stream));
         }
         FLORA_HIP(hipMalloc(&p->d_table, p->table_bytes));
         p->table_cap = p->table_bytes;
@@ -442,7 +506,13 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     if (st != FLORA_OK) return st;
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
-    if (variant == 2) FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, s));
+    if (variant == 2) {
+        float* partials = static_cast<float*>(p->d_work);
+        uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
+                                                                   round_up(p->ws_floats * 4, 256))
+                                       : nullptr;
+        FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, partials, counters, s));
+    }
     else {
         const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : 2;
         FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, p->mt, s));
@@ -716,8 +786,11 @@ int flora_set_tuning(const char* name, int value)
     } else if (std::strcmp(name, "compress_f32_mt") == 0) {
         if (value != 0 && value != 1 && value != 2) return FLORA_ERR_INVALID;
         g_tune.compress_f32_mt = value;
+    } else if (std::strcmp(name, "compress_splitk_cols") == 0) {
+        if (value < 0 || (value % 64) != 0) return FLORA_ERR_INVALID;
+        g_tune.compress_splitk_cols = value;
     } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
-        if (!pow2_124 && value != 8) return FLORA_ERR_INVALID;
+        if (!pow2_124 && value != 8 && value != 16) return FLORA_ERR_INVALID;
         g_tune.compress_bf16_mt = value;
     } else if (std::strcmp(name, "decompress_vec") == 0) {
         if (value < 0 || value > 2) return FLORA_ERR_INVALID;

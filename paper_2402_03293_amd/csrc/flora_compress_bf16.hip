@@ -191,17 +191,22 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 constexpr int kWBK = 64;             // columns of G per tile
 constexpr int kWLda = kWBK + 8;      // padded LDS row (bf16 elements): 144 bytes
 
-template <int CT>   // 16-wide column tiles per wave: RS = 16 CT
+template <int CT, int RT>   // per wave: CT 16-wide column tiles (RS = 16 CT), RT 16-row tiles
 __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* __restrict__ mats,
                                                                  const WorkItem* __restrict__ items,
-                                                                 const SeedArgs seeds, int R, float a, float b)
+                                                                 const SeedArgs seeds, int R, float a, float b,
+                                                                 float* __restrict__ partials,
+                                                                 uint32_t* __restrict__ counters)
 {
+    constexpr int WR = 16 * RT;      // rows of one wave
+    constexpr int BR = 8 * WR;       // rows of the workgroup
     constexpr int RS = 16 * CT;      // rank columns of this workgroup
     constexpr int NQ = RS / 32;      // quads per thread and tile when generating
     constexpr int JG = kWBK / NQ;    // threads along j when generating (each takes NQ columns j)
     constexpr int LDE = RS + 4;      // padded row of the epilogue staging (floats)
     constexpr int kABytes = 2 * RS * kWLda * 2;
     constexpr int kEBytes = 8 * 16 * LDE * 4;
+    __shared__ uint32_t lds_flag;
     __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kABytes > kEBytes ? kABytes : kEBytes];
     typedef uint16_t (*lds_a_t)[RS][kWLda];
     lds_a_t ldsA = reinterpret_cast<lds_a_t>(lds_raw);
@@ -218,28 +223,31 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, g = lane >> 4;
     const float cgen = neg2_ln2_over(R);
-    const int ntiles = (int)((m + kWBK - 1) / kWBK);
+    // this workgroup's share of the columns: tiles [tile0, ntiles)
+    const long long col_end = (it.col1 < m) ? (long long)it.col1 : m;
+    const int tile0 = it.col0 / kWBK;
+    const int ntiles = (int)((col_end + kWBK - 1) / kWBK);
     const uint32_t q0 = (uint32_t)(it.slice * (RS / 4));   // first Philox quad of this rank slice
     const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
-    const long long wave_row0 = (long long)it.row0 + wave * 64;
+    const long long wave_row0 = (long long)it.row0 + wave * WR;
 
-    // One buffer resource for the 64 rows of this wave, covering exactly its valid rows:
+    // One buffer resource for the WR rows of this wave, covering exactly its valid rows:
     // rows past the end and (through kOob) columns past m read as zero.
     long long valid = row_end - wave_row0;
-    valid = valid < 0 ? 0 : (valid > 64 ? 64 : valid);
+    valid = valid < 0 ? 0 : (valid > WR ? WR : valid);
     const rsrc_t rs = make_rsrc(G + (wave_row0 < n ? wave_row0 : 0) * m, valid * m * 2);
-    uint32_t lane_off[4];
+    uint32_t lane_off[RT];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) lane_off[rt] = ((uint32_t)(16 * rt + li) * (uint32_t)m + 8u * (uint32_t)g) * 2u;
+    for (int rt = 0; rt < RT; ++rt) lane_off[rt] = ((uint32_t)(16 * rt + li) * (uint32_t)m + 8u * (uint32_t)g) * 2u;
 
     // Chunk (s, g) of a tile holds columns j0 + 32 s + 8 g .. + 7; m % 8 == 0, so a chunk is
     // all in or all out.  Out-of-range chunks are pointed at kOob and fetch nothing.
-    auto load_half = [&](v4u (&dst)[4][2], int tile, int s) {
+    auto load_half = [&](v4u (&dst)[RT][2], int tile, int s) {
         const uint32_t col = (uint32_t)tile * kWBK + 32u * (uint32_t)s + 8u * (uint32_t)g;
-        const bool ok = col < (uint32_t)m;
+        const bool ok = col < (uint32_t)col_end;
         const uint32_t coff = ((uint32_t)tile * kWBK + 32u * (uint32_t)s) * 2u;
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) dst[rt][s] = buf_load_u4(rs, ok ? lane_off[rt] + coff : kOob);
+        for (int rt = 0; rt < RT; ++rt) dst[rt][s] = buf_load_u4(rs, ok ? lane_off[rt] + coff : kOob);
     };
 
     // 64 x RS normals per tile = 16 RS quads, NQ per thread: thread p takes quad index
@@ -270,9 +278,9 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    f32x4 acc[4][CT];
+    f32x4 acc[RT][CT];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -280,7 +288,7 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     // columns) at a time; the B operand of column tile ct + 1 is fetched from LDS while tile
     // ct multiplies.  As soon as the MFMAs of a half are issued its registers are refilled
     // with the tile two steps ahead.
-    auto mfma_tile = [&](v4u (&gt)[4][2], int buf, int tile) {
+    auto mfma_tile = [&](v4u (&gt)[RT][2], int buf, int tile) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsA[buf][li][32 * s + 8 * g]);
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
                 bf16x8 bn = bv;
                 if (ct + 1 < CT) bn = *reinterpret_cast<const bf16x8*>(&ldsA[buf][16 * (ct + 1) + li][32 * s + 8 * g]);
 #pragma unroll
-                for (int rt = 0; rt < 4; ++rt)
+                for (int rt = 0; rt < RT; ++rt)
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, gt[rt][s]), bv,
                                                                           acc[rt][ct], 0, 0, 0);
                 bv = bn;
@@ -312,15 +320,15 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         if (mine && tile < ntiles) gen_tile(buf, tile);
     };
 
-    v4u gx[4][2], gy[4][2];
-    load_half(gx, 0, 0);
-    load_half(gx, 0, 1);
-    load_half(gy, 1, 0);
-    load_half(gy, 1, 1);
-    gen_tile(0, 0);
-    gen_if(early, 1, 1);
+    v4u gx[RT][2], gy[RT][2];
+    load_half(gx, tile0, 0);
+    load_half(gx, tile0, 1);
+    load_half(gy, tile0 + 1, 0);
+    load_half(gy, tile0 + 1, 1);
+    gen_tile(0, tile0);
+    gen_if(early, 1, tile0 + 1);
     __syncthreads();
-    for (int tile = 0; tile < ntiles; tile += 2) {
+    for (int tile = tile0; tile < ntiles; tile += 2) {
         mfma_tile(gx, 0, tile);
         gen_if(!early, 1, tile + 1);
         __syncthreads();
@@ -335,16 +343,29 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     // Epilogue.  D layout of a 16x16 tile: lane holds column lane % 16 and, in register v,
     // row 4 * (lane / 16) + v.  Each wave writes one 16 x RS block of rows at a time to its own
     // staging area and reads it back so that a lane holds four consecutive rank columns of
-    // one row: the state is then read and written 16 bytes per lane, RS * 4 contiguous
-    // bytes per row.  The state's buffer resource ends at the last valid row of this wave.
+    // one row: memory is then accessed 16 bytes per lane, RS * 4 contiguous bytes per row.
+    //
+    // A workgroup that owns all columns of its rows updates the state directly.  When the
+    // columns of a row block are shared between nparts workgroups (short launches, to fill
+    // the chip), each stores its partial product; the one that finishes last adds the
+    // partials in the order 0 .. nparts - 1, whoever it is, and updates the state, so the
+    // result does not depend on timing.
     float* stage = reinterpret_cast<float*>(lds_raw) + wave * (16 * LDE);
-    const rsrc_t st_rs = make_rsrc(state + (wave_row0 < n ? wave_row0 : 0) * R, valid * R * 4);
     constexpr int LPR = RS / 4;           // lanes per row when reading back
     constexpr int RPI = 64 / LPR;         // rows per instruction
     constexpr int NP = 16 / RPI;          // passes per block of 16 rows
     const int erow = lane / LPR, echunk = lane % LPR;
+    const bool split = it.nparts > 1;
+    // direct: the state's buffer resource ends at the last valid row of this wave;
+    // split: this part's BR x RS block of the partial area (always whole)
+    float* pbase = partials + (size_t)it.poff + (size_t)it.part * (BR * RS) + (size_t)wave * (WR * RS);
+    const rsrc_t st_rs = split ? make_rsrc(pbase, (long long)WR * RS * 4)
+                               : make_rsrc(state + (wave_row0 < n ? wave_row0 : 0) * R, valid * R * 4);
+    const uint32_t row_stride = split ? (uint32_t)RS : (uint32_t)R;
+    const uint32_t col_base = split ? 0u : (uint32_t)(it.slice * RS);
+    const bool rmw = !split && a != 0.f;
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -355,33 +376,75 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         uint32_t goff[NP];
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            const int row = 16 * rt + erow + RPI * p;     // row within the wave's 64
-            goff[p] = ((uint32_t)row * (uint32_t)R + (uint32_t)(it.slice * RS + 4 * echunk)) * 4u;
-            oldv[p] = (a != 0.f) ? buf_load_f4(st_rs, goff[p]) : v4f{0.f, 0.f, 0.f, 0.f};
+            const int row = 16 * rt + erow + RPI * p;     // row within the wave's rows
+            goff[p] = ((uint32_t)row * row_stride + col_base + 4u * (uint32_t)echunk) * 4u;
+            oldv[p] = rmw ? buf_load_f4(st_rs, goff[p]) : v4f{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const v4f nv = *reinterpret_cast<const v4f*>(&stage[(erow + RPI * p) * LDE + 4 * echunk]);
-            const v4f res = {a * oldv[p].x + b * nv.x, a * oldv[p].y + b * nv.y, a * oldv[p].z + b * nv.z,
-                             a * oldv[p].w + b * nv.w};
-            buf_store_f4(st_rs, goff[p], res);
+            if (split) {
+                // written through to memory (device scope): another XCD's L2 never sees a stale copy
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, nv), st_rs, (int)goff[p], 0, 16);
+            } else {
+                buf_store_f4(st_rs, goff[p], v4f{a * oldv[p].x + b * nv.x, a * oldv[p].y + b * nv.y,
+                                                 a * oldv[p].z + b * nv.z, a * oldv[p].w + b * nv.w});
+            }
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);   // reads done before the next block overwrites the area
     }
+    if (!split) return;
+
+    // ---- shared columns: count arrivals; the last one combines.  The partials are stored and
+    // loaded with device scope on the accesses themselves (write-through / L2-bypassing), so
+    // no cache-wide release or acquire is needed: a store is visible once it has completed.
+    __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0): this thread's partial stores have completed ...
+    __syncthreads();                          // ... and so have everybody's, before the arrival is counted
+    if (tid == 0) lds_flag = atomicAdd(counters + it.cidx, 1u);
+    __syncthreads();
+    if (lds_flag != (uint32_t)(it.nparts - 1)) return;
+    const float* gbase = partials + (size_t)it.poff;
+    const rsrc_t prs = make_rsrc(gbase, (long long)it.nparts * BR * RS * 4);
+    const long long rows_here = row_end - it.row0;          // valid rows of the block
+    const int nvec = (int)rows_here * (RS / 4);
+    for (int f = tid; f < nvec; f += 512) {
+        const int row = f / (RS / 4), c4 = f % (RS / 4);
+        v4f sum = {0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < it.nparts; ++q) {
+            // device-coherent load: the other parts were written by other compute units
+            const v4f pv = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(
+                prs, (int)(((uint32_t)q * (BR * RS) + (uint32_t)row * RS + 4u * (uint32_t)c4) * 4u), 0, 16));
+            sum.x += pv.x; sum.y += pv.y; sum.z += pv.z; sum.w += pv.w;
+        }
+        float* sp = state + ((long long)it.row0 + row) * R + it.slice * RS + 4 * c4;
+        v4f o = {0.f, 0.f, 0.f, 0.f};
+        if (a != 0.f) o = ldg4(sp);
+        *(FLORA_GLOBAL v4f*)sp = v4f{a * o.x + b * sum.x, a * o.y + b * sum.y,
+                                                        a * o.z + b * sum.z, a * o.w + b * sum.w};
+    }
+    if (tid == 0) counters[it.cidx] = 0u;     // every part has arrived: ready for the next launch
 }
 
 }  // namespace
 
-// All items of one launch share one MT (rows per workgroup = 128 * MT), chosen by the host.
+// All items of one launch share one MT (rows per workgroup = 128 * MT; 8 and 16 select the wide
+// kernel), chosen by the host.  partials / counters: workspace of the wide kernel's shared-column
+// mode (may be null when no item has nparts > 1).
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
-                                   const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s)
+                                   const SeedArgs& seeds, int r, int mt, float a, float b, float* partials,
+                                   uint32_t* counters, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
-    if (mt == 8) {   // wide kernel: 512 rows per workgroup, rank slices of 128 (64 at r = 64)
+    if (mt == 8 || mt == 16) {   // wide kernel: 512 (8) or 256 (16) rows per workgroup, rank slices of 128 (64 at r = 64)
         const dim3 grid((unsigned)nitems), block(512);
-        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        if (mt == 8) {
+            if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+            else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        } else {
+            if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 2>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+            else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        }
         return hipGetLastError();
     }
     const dim3 grid((unsigned)nitems), block(256);

@@ -39,6 +39,11 @@ struct WorkItem {
     int col0;    // first column (decompress) / unused
     int slice;   // rank slice index (compress at r >= 128) / column-chunk index
     int rblock;  // row-block index within the matrix
+    // wide bf16 compress only: this workgroup's columns [col0, col1) are part `part` of `nparts`
+    // of its (row block, rank slice); with nparts > 1 the partial products live at float offset
+    // `poff` of the workspace and arrivals are counted in counter `cidx`
+    int col1, part, nparts, cidx;
+    long long poff;
 };
 
 enum DecompressMode : int {
@@ -147,7 +152,8 @@ hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStr
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                int r, int grad_is_bf16, float a, float b, int kgroups, int mt, hipStream_t s);
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
-                                   const SeedArgs& seeds, int r, int mt, float a, float b, hipStream_t s);
+                                   const SeedArgs& seeds, int r, int mt, float a, float b, float* partials,
+                                   uint32_t* counters, hipStream_t s);
 hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
 hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,

@@ -139,9 +139,10 @@ def test_compress_bf16_path(n, m, r):
 
 
 # every launch shape of the bf16 compress kernel, forced through the tuning hook: the narrow
-# kernel (128 / 256 / 512 rows per workgroup) and the wide one (8: 512 rows, rank slices of 128),
+# kernel (128 / 256 / 512 rows per workgroup) and the wide one (8 / 16: 512 / 256 rows, rank slices
+# of 128),
 # on shapes with ragged row blocks, a ragged last column tile and odd / even tile counts
-@pytest.mark.parametrize("mt", [1, 2, 4, 8])
+@pytest.mark.parametrize("mt", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("n,m,r", [(700, 520, 256), (1100, 64, 128), (97, 1160, 64), (513, 200, 256)])
 def test_compress_bf16_every_launch_shape(n, m, r, mt):
     seed = 2500 + n + m + r
@@ -164,6 +165,40 @@ def test_compress_bf16_every_launch_shape(n, m, r, mt):
     # row by row as well: a wrong row block would hide in the Frobenius norm of a large matrix
     rows = np.linalg.norm(to64(st2) - ref2, axis=1) / np.linalg.norm(ref2, axis=1)
     assert rows.max() < TOL_BF16, (int(rows.argmax()), float(rows.max()))
+
+
+# the wide kernel with the columns of a row block shared between workgroups (partial products
+# combined by the last workgroup to arrive): several parts, ragged last part, two launches in a
+# row on the same descriptor set (the arrival counters must be back at zero), grouped matrices
+@pytest.mark.parametrize("mt", [8, 16])
+@pytest.mark.parametrize("kc", [64, 192, 448])
+@pytest.mark.parametrize("r", [64, 256])
+def test_compress_bf16_shared_columns(r, kc, mt):
+    shapes = [(300, 520), (520, 1160), (64, 64), (257, 200)]
+    seeds = [2700 + r + l for l in range(len(shapes))]
+    Gs = [[rand(s, 2800 + 10 * step + l, torch.bfloat16) for l, s in enumerate(shapes)] for step in range(2)]
+    states = [torch.zeros((n, r), device=DEV) for n, _ in shapes]
+    flora.set_tuning("compress_bf16_mt", mt)
+    flora.set_tuning("compress_splitk_cols", kc)
+    try:
+        mats = flora.matrices(shapes, grads=Gs[0], states=states, seeds=seeds)
+        flora.compress(mats, r, flora.BF16, 0.0, 1.0)
+        first = [st.clone() for st in states]
+        flora.compress(mats, r, flora.BF16, 0.5, 2.0)          # same plan, same gradients
+        mats2 = flora.matrices(shapes, grads=Gs[1], states=states, seeds=seeds)
+        flora.compress(mats2, r, flora.BF16, 1.0, 1.0)
+        sync()
+    finally:
+        flora.set_tuning("compress_bf16_mt", 0)
+        flora.set_tuning("compress_splitk_cols", 0)
+    for l, (n, m) in enumerate(shapes):
+        ref1 = oracle.compress(to64(Gs[0][l]), r, seeds[l])
+        e1 = rel_fro(to64(first[l]), ref1)
+        assert e1 < 6e-3, (l, e1)
+        rows = np.linalg.norm(to64(first[l]) - ref1, axis=1) / np.linalg.norm(ref1, axis=1)
+        assert rows.max() < TOL_BF16, (l, int(rows.argmax()), float(rows.max()))
+        ref = oracle.compress(to64(Gs[1][l]), r, seeds[l], state=2.5 * ref1)
+        assert rel_fro(to64(states[l]), ref) < 6e-3
 
 
 def test_compress_grouped_many_matrices_and_accumulation():
