@@ -56,7 +56,8 @@ struct Plan {
     std::vector<WorkItem> items2;       // transfer: state <- state T table
     int mt = 1;                         // bf16 compress: rows per workgroup = 128 * mt
     int vec = 0;                        // decompress: the 16-byte-per-lane bf16 kernel (256-column workgroups)
-    size_t ws_floats = 0;               // wide bf16 compress: floats of partial products (shared-column mode)
+    int kc = 0;                         // fp32 compress: columns per part (0: whole rows)
+    size_t ws_floats = 0;               // compress: floats of partial products (shared-column mode)
     size_t ws_counters = 0;             // ... and arrival counters
     void* d_table = nullptr;            // MatDev[count] + items + items2
     size_t table_cap = 0;
@@ -104,15 +105,44 @@ void build_compress_f32_items(Plan& p)
                      [&](int a, int b) { return p.host_mats[a].m > p.host_mats[b].m; });
     p.mt = g_tune.compress_f32_mt ? g_tune.compress_f32_mt : 1;
     const int rows_per_wg = 64 * p.mt;
+    const int rp = (p.r + 15) / 16 * 16;
+    // A workgroup streams through one compute unit's load path, which carries about an eighth
+    // of a percent of the chip's bandwidth: in a launch of a few thousand row blocks the
+    // long ones would finish last and alone.  Their columns are then shared between
+    // workgroups of about 512 columns (partial products combined by the last one to finish;
+    // nparts * rows * r * 8 bytes of extra traffic per block, little at these ranks).
+    long long kc = g_tune.compress_splitk_cols;
+    if (kc == 0) {
+        long long blocks = 0;
+        for (int l = 0; l < p.count; ++l) blocks += (p.host_mats[l].n + rows_per_wg - 1) / rows_per_wg;
+        if (blocks < 8192) kc = 512;
+    }
+    p.kc = (int)kc;
+    p.ws_floats = 0;
+    p.ws_counters = 0;
     for (int l : order) {
-        const long long n = p.host_mats[l].n;
+        const long long n = p.host_mats[l].n, m = p.host_mats[l].m;
+        int parts = kc > 0 ? (int)((m + kc - 1) / kc) : 1;
+        const long long pcols = ((m + parts - 1) / parts + 63) / 64 * 64;
+        parts = (int)((m + pcols - 1) / pcols);
         int rb = 0;
         for (long long r0 = 0; r0 < n; r0 += rows_per_wg, ++rb) {
-            WorkItem w{};
-            w.mat = l; w.row0 = (int)r0;
-            w.rows = (int)std::min<long long>(rows_per_wg, n - r0);
-            w.rblock = rb;
-            p.items.push_back(w);
+            const long long poff = (long long)p.ws_floats;
+            const int cidx = (int)p.ws_counters;
+            if (parts > 1) {
+                p.ws_floats += (size_t)parts * rows_per_wg * rp;
+                p.ws_counters += 1;
+            }
+            for (int part = 0; part < parts; ++part) {
+                WorkItem w{};
+                w.mat = l; w.row0 = (int)r0;
+                w.rows = (int)std::min<long long>(rows_per_wg, n - r0);
+                w.rblock = rb;
+                w.col0 = (int)(part * pcols);
+                w.col1 = (int)std::min<long long>(m, (part + 1) * pcols);
+                w.part = part; w.nparts = parts; w.poff = poff; w.cidx = cidx;
+                p.items.push_back(w);
+            }
         }
     }
 }
@@ -514,8 +544,14 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
         FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, partials, counters, s));
     }
     else {
-        const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : 2;
-        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, p->mt, s));
+        // column groups per workgroup: two for whole rows; one when the pieces are 512 columns
+        const int kg = g_tune.compress_f32_kgroups ? g_tune.compress_f32_kgroups : (p->kc > 0 ? 1 : 2);
+        float* partials = static_cast<float*>(p->d_work);
+        uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
+                                                                   round_up(p->ws_floats * 4, 256))
+                                       : nullptr;
+        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, p->mt, partials,
+                                      counters, s));
     }
     return FLORA_OK;
 }

@@ -56,7 +56,9 @@ __device__ __forceinline__ v4f load4(const uint16_t* rowp, long long col, long l
 template <int R, typename GT, int MT, int KG>
 __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __restrict__ mats,
                                                                 const WorkItem* __restrict__ items,
-                                                                const SeedArgs seeds, float a, float b)
+                                                                const SeedArgs seeds, float a, float b,
+                                                                float* __restrict__ partials,
+                                                                uint32_t* __restrict__ counters)
 {
     constexpr int NT = (R + 15) / 16;   // 16-wide column tiles of the state
     constexpr int RP = NT * 16;
@@ -80,7 +82,10 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
     const int li = lane & 15, g = lane >> 4;
     const float cgen = neg2_ln2_over(R);
     const bool vec_ok = (m % 4) == 0;
-    const int ntiles = (int)((m + kBK - 1) / kBK);
+    // this workgroup's share of the columns: [col0, col_end), tiles tbase .. tbase + ntiles - 1
+    const long long col_end = (it.col1 < m) ? (long long)it.col1 : m;
+    const int tbase = it.col0 / kBK;
+    const int ntiles = (int)((col_end - it.col0 + kBK - 1) / kBK);
     const int iters = (ntiles + KG - 1) / KG;       // tiles per group (the last may be missing)
 
     if (R < RP) {   // rank 8: the upper half of the 16-wide tile is zero padding
@@ -117,12 +122,12 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
     const uint32_t lane_off = ((uint32_t)li * (uint32_t)m + 4u * (uint32_t)g) * ESZ;
 
     auto load_tile_fast = [&](v4f (&dst)[MT][4], int i) {
-        const int tile = kg + KG * i;
-        // a round past the end has tile >= ntiles, so its columns fail the same test
+        const int tile = tbase + kg + KG * i;
+        // a round past the end has a tile past the last one, so its columns fail the same test
         const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const bool ok = col0 + 16u * c < (uint32_t)m;
+            const bool ok = col0 + 16u * c < (uint32_t)col_end;
             const uint32_t off = ok ? lane_off + ((uint32_t)tile * kBK + 16u * c) * ESZ : kOob;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
 
     auto gen_tile = [&](int buf, int i) {
         constexpr int QT = kBK * (R / 4);
-        const long long j0 = (long long)(kg + KG * i) * kBK;
+        const long long j0 = (long long)(tbase + kg + KG * i) * kBK;
 #pragma unroll
         for (int idx0 = 0; idx0 < QT; idx0 += 256) {
             const int idx = idx0 + tg;
@@ -187,17 +192,18 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         for (int u = 0; u < kPF - 1; ++u) load_tile_fast(st[u], u);
         gen_tile(0, 0);
         __syncthreads();
+        // The body is free of branches around memory operations (a round past the end loads
+        // nothing, multiplies zeros and skips only the generator): the compiler can then
+        // follow the outstanding loads around the loop and waits for the oldest stage alone.
         for (int base = 0; base < fast_rounds; base += kPF) {
 #pragma unroll
             for (int u = 0; u < kPF; ++u) {
                 const int i = base + u;
-                if (i < fast_rounds) {
-                    const int buf = i & 1;
-                    load_tile_fast(st[(u + kPF - 1) % kPF], i + kPF - 1);
-                    if (i + 1 < fast_rounds) gen_tile(buf ^ 1, i + 1);
-                    mfma_tile(st[u], buf);
-                    __syncthreads();
-                }
+                const int buf = i & 1;
+                load_tile_fast(st[(u + kPF - 1) % kPF], i + kPF - 1);
+                if (i + 1 < fast_rounds) gen_tile(buf ^ 1, i + 1);
+                mfma_tile(st[u], buf);
+                __syncthreads();
             }
         }
     }
@@ -206,11 +212,11 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         const bool active = tile < ntiles;
         v4f gt[MT][4];
         if (active) {
-            const long long j0 = (long long)tile * kBK;
+            const long long j0 = (long long)(tbase + tile) * kBK;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) gt[mt][c] = load4(rowp[mt], j0 + 16 * c + 4 * g, m, false);
+                for (int c = 0; c < 4; ++c) gt[mt][c] = load4(rowp[mt], j0 + 16 * c + 4 * g, col_end, false);
             gen_tile(0, i);
         }
         __syncthreads();
@@ -244,6 +250,48 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
                         acc[mt][nt][v] += ldsRed[k2][wave * (MT * 16) + mt * 16 + 4 * g + v][nt * 16 + li];
     }
 
+    if (it.nparts > 1) {
+        // The columns of this row block are shared between nparts workgroups (short launches:
+        // equal pieces of work spread over the chip).  Each stores its partial product with
+        // device scope on the stores themselves; the last to arrive adds the partials in the
+        // order 0 .. nparts - 1, whoever it is, and updates the state: no float atomics, the
+        // result does not depend on timing.
+        __shared__ uint32_t lds_flag;
+        float* pb = partials + (size_t)it.poff + (size_t)it.part * (ROWS * RP);
+        const rsrc_t prs_w = make_rsrc(pb, (long long)ROWS * RP * 4);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t row = (uint32_t)(wave * (MT * 16) + mt * 16 + 4 * g + v);
+                    const float val = acc[mt][nt][v];
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), prs_w,
+                                                          (int)((row * RP + nt * 16 + li) * 4u), 0, 16);
+                }
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0): this thread's partial stores have completed
+        __syncthreads();                      // (only column group 0 is left: 256 threads)
+        if (tg == 0) lds_flag = atomicAdd(counters + it.cidx, 1u);
+        __syncthreads();
+        if (lds_flag != (uint32_t)(it.nparts - 1)) return;
+        const rsrc_t prs = make_rsrc(partials + (size_t)it.poff, (long long)it.nparts * ROWS * RP * 4);
+        long long rows_here = n - it.row0;
+        rows_here = rows_here > it.rows ? it.rows : rows_here;
+        for (int f = tg; f < (int)rows_here * R; f += 256) {
+            const int row = f / R, k = f % R;
+            float sum = 0.f;
+            for (int q = 0; q < it.nparts; ++q)
+                sum += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                           prs, (int)(((uint32_t)q * (ROWS * RP) + (uint32_t)row * RP + (uint32_t)k) * 4u), 0, 16));
+            float* sp = state + ((long long)it.row0 + row) * R + k;
+            const float o = (a != 0.f) ? ldg(sp) : 0.f;
+            stg(sp, a * o + b * sum);
+        }
+        if (tg == 0) counters[it.cidx] = 0u;   // every part has arrived: ready for the next launch
+        return;
+    }
+
     // All old values are fetched first (clamped addresses), then the new ones are stored.
     float old[MT][NT][4];
 #pragma unroll
@@ -273,13 +321,13 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
 
 template <int R, typename GT, int MT>
 hipError_t launch_mt(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                     float a, float b, int kgroups, hipStream_t s)
+                     float a, float b, int kgroups, float* partials, uint32_t* counters, hipStream_t s)
 {
     const dim3 grid((unsigned)nitems);
     switch (kgroups) {
-    case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1>), grid, dim3(256), 0, s, mats, items, seeds, a, b); break;
-    case 2: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 2>), grid, dim3(512), 0, s, mats, items, seeds, a, b); break;
-    case 4: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 4>), grid, dim3(1024), 0, s, mats, items, seeds, a, b); break;
+    case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1>), grid, dim3(256), 0, s, mats, items, seeds, a, b, partials, counters); break;
+    case 2: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 2>), grid, dim3(512), 0, s, mats, items, seeds, a, b, partials, counters); break;
+    case 4: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 4>), grid, dim3(1024), 0, s, mats, items, seeds, a, b, partials, counters); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -287,27 +335,28 @@ hipError_t launch_mt(const MatDev* mats, const WorkItem* items, int nitems, cons
 
 template <int R, typename GT>
 hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                      float a, float b, int kgroups, int mt, hipStream_t s)
+                      float a, float b, int kgroups, int mt, float* partials, uint32_t* counters, hipStream_t s)
 {
-    if (mt == 1) return launch_mt<R, GT, 1>(mats, items, nitems, seeds, a, b, kgroups, s);
-    if (mt == 2) return launch_mt<R, GT, 2>(mats, items, nitems, seeds, a, b, kgroups, s);
+    if (mt == 1) return launch_mt<R, GT, 1>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+    if (mt == 2) return launch_mt<R, GT, 2>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, hipStream_t s)
+                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, float* partials,
+                               uint32_t* counters, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (!grad_is_bf16) {
-        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
-        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
-        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
     } else {
-        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
-        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
-        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, s);
+        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
     }
     return hipErrorInvalidValue;
 }

@@ -39,7 +39,7 @@ struct WorkItem {
     int col0;    // first column (decompress) / unused
     int slice;   // rank slice index (compress at r >= 128) / column-chunk index
     int rblock;  // row-block index within the matrix
-    // wide bf16 compress only: this workgroup's columns [col0, col1) are part `part` of `nparts`
+    // fp32 and wide bf16 compress: this workgroup's columns [col0, col1) are part `part` of `nparts`
     // of its (row block, rank slice); with nparts > 1 the partial products live at float offset
     // `poff` of the workspace and arrivals are counted in counter `cidx`
     int col1, part, nparts, cidx;
@@ -150,7 +150,8 @@ hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out
                                  hipStream_t s);
 hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s);
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, hipStream_t s);
+                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, float* partials,
+                               uint32_t* counters, hipStream_t s);
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
                                    const SeedArgs& seeds, int r, int mt, float a, float b, float* partials,
                                    uint32_t* counters, hipStream_t s);

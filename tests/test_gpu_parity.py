@@ -201,6 +201,34 @@ def test_compress_bf16_shared_columns(r, kc, mt):
         assert rel_fro(to64(states[l]), ref) < 6e-3
 
 
+# the fp32 matrix-core kernel with shared columns, every rank, both gradient types, 1 / 2 / 4
+# column groups per workgroup, ragged parts, two launches in a row on one descriptor set
+@pytest.mark.parametrize("kg", [1, 2, 4])
+@pytest.mark.parametrize("r,gdt", [(8, "f32"), (16, "f32"), (32, "bf16"), (16, "bf16")])
+def test_compress_fp32_path_shared_columns(r, gdt, kg):
+    shapes = [(130, 520), (64, 1160), (33, 64), (200, 203)]
+    tdt = torch.float32 if gdt == "f32" else torch.bfloat16
+    fdt = flora.F32 if gdt == "f32" else flora.BF16
+    seeds = [2900 + r + l for l in range(len(shapes))]
+    Gs = [rand(s_, 2950 + l, tdt) for l, s_ in enumerate(shapes)]
+    states = [torch.full((n, r), float("nan"), device=DEV) for n, _ in shapes]
+    flora.set_tuning("compress_f32_kgroups", kg)
+    flora.set_tuning("compress_splitk_cols", 128)
+    try:
+        mats = flora.matrices(shapes, grads=Gs, states=states, seeds=seeds)
+        flora.compress(mats, r, fdt, 0.0, 1.0)
+        flora.compress(mats, r, fdt, 0.5, 2.0)
+        sync()
+    finally:
+        flora.set_tuning("compress_f32_kgroups", 0)
+        flora.set_tuning("compress_splitk_cols", 0)
+    for l in range(len(shapes)):
+        ref = 2.5 * oracle.compress(to64(Gs[l]), r, seeds[l])
+        assert rel_fro(to64(states[l]), ref) < TOL_F32, l
+        rows = np.linalg.norm(to64(states[l]) - ref, axis=1) / np.linalg.norm(ref, axis=1)
+        assert rows.max() < 5 * TOL_F32, (l, int(rows.argmax()), float(rows.max()))
+
+
 def test_compress_grouped_many_matrices_and_accumulation():
     shapes = [(96, 128), (64, 300), (130, 64), (32, 32), (200, 72)]
     r, tau = 16, 3
