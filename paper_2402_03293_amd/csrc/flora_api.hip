@@ -284,25 +284,51 @@ void build_decompress_items(Plan& p)
     p.vec = vec;
     const int cols = vec ? kDecompressColsVec : kDecompressCols;
     const int rows_per_wg = choose_decompress_rows(p.host_mats, cols);
+    struct Group { int mat, rb, row0, rows, nchunks; };
+    std::vector<Group> groups;
     for (int l = 0; l < p.count; ++l) {
         MatDev& M = p.host_mats[l];
         M.nrowblocks = (int)((M.n + rows_per_wg - 1) / rows_per_wg);
         M.ncolchunks = (int)((M.m + cols - 1) / cols);
-        M.item0 = (int)p.items.size();
         // equal row blocks, a multiple of 32 rows each
         long long per = (M.n + M.nrowblocks - 1) / M.nrowblocks;
         per = (per + 31) / 32 * 32;
         M.nrowblocks = (int)((M.n + per - 1) / per);
+        M.item0 = 0;
+        M.nitems = M.nrowblocks * M.ncolchunks;
         for (int rb = 0; rb < M.nrowblocks; ++rb)
-            for (int cc = 0; cc < M.ncolchunks; ++cc) {
+            groups.push_back(Group{l, rb, (int)(rb * per), (int)std::min<long long>(per, M.n - rb * per), M.ncolchunks});
+    }
+    // Every workgroup of a row block reads that block of the state.  Workgroup ids go
+    // round-robin over the 8 XCDs, each with its own L2: if the column chunks of one row
+    // block simply followed each other, every XCD would fetch every state block from HBM
+    // (8 times the state's size; at r = 256 that was a third of the kernel's traffic).  So
+    // row blocks are taken eight at a time (with equal chunk counts) and their chunks
+    // interleaved: all chunks of one row block get ids equal modulo 8, close together, and
+    // find the block in their XCD's L2 after the first.  Row blocks that do not fill a
+    // bundle of eight come last.
+    std::stable_sort(groups.begin(), groups.end(), [](const Group& a, const Group& b) { return a.nchunks > b.nchunks; });
+    auto emit = [&](const Group* g, size_t ng) {
+        for (int cc = 0; cc < g[0].nchunks; ++cc)
+            for (size_t x = 0; x < ng; ++x) {
+                if (cc >= g[x].nchunks) continue;
                 WorkItem w{};
-                w.mat = l; w.row0 = (int)(rb * per);
-                w.rows = (int)std::min<long long>(per, M.n - w.row0);
-                w.col0 = cc * cols; w.slice = cc; w.rblock = rb;
+                w.mat = g[x].mat; w.row0 = g[x].row0; w.rows = g[x].rows;
+                w.col0 = cc * cols; w.slice = cc; w.rblock = g[x].rb;
+                w.part = g[x].rb * g[x].nchunks + cc;
                 p.items.push_back(w);
             }
-        M.nitems = (int)p.items.size() - M.item0;
+    };
+    std::vector<Group> rest;
+    for (size_t i = 0; i < groups.size();) {
+        size_t j = i;
+        while (j < groups.size() && groups[j].nchunks == groups[i].nchunks) ++j;
+        size_t k = i;
+        for (; k + 8 <= j; k += 8) emit(&groups[k], 8);
+        for (; k < j; ++k) rest.push_back(groups[k]);
+        i = j;
     }
+    for (size_t k = 0; k < rest.size(); k += 8) emit(&rest[k], std::min<size_t>(8, rest.size() - k));
 }
 
 void build_apply_T_items(Plan& p)

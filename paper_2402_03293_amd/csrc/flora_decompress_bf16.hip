@@ -410,7 +410,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         if (lane == 0) lds_fin[wave] = t;
         __syncthreads();
         if (tid == 0)
-            M.itempart[(int)blockIdx.x - M.item0] = ((lds_fin[0] + lds_fin[1]) + (lds_fin[2] + lds_fin[3])) +
+            M.itempart[it.part] = ((lds_fin[0] + lds_fin[1]) + (lds_fin[2] + lds_fin[3])) +
                                                     ((lds_fin[4] + lds_fin[5]) + (lds_fin[6] + lds_fin[7]));
     }
 }

@@ -171,7 +171,7 @@ __device__ __forceinline__ void epilogue_end(const MatDev& M, const WorkItem& it
         if (lane == 0) lds_red[wave][0] = s;
         __syncthreads();
         if (tid == 0)
-            M.itempart[(int)blockIdx.x - M.item0] =
+            M.itempart[it.part] =
                 ((lds_red[0][0] + lds_red[1][0]) + lds_red[2][0]) + lds_red[3][0];
     }
 }

@@ -21,7 +21,7 @@ struct MatDev {
     long long n, m;
     uint32_t seed_lo, seed_hi, seedn_lo, seedn_hi;   // used by the transfer kernels only
     int ncolchunks, nrowblocks;   // decompress tiling of this matrix
-    int item0, nitems;            // this matrix's range in the decompress work table
+    int item0, nitems;            // number of decompress workgroups of this matrix (item0: unused)
 };
 
 // Seeds of the matrices of one grouped launch, passed by value as a kernel argument:
@@ -39,6 +39,7 @@ struct WorkItem {
     int col0;    // first column (decompress) / unused
     int slice;   // rank slice index (compress at r >= 128) / column-chunk index
     int rblock;  // row-block index within the matrix
+    // decompress: `part` = this workgroup's slot in its matrix's per-workgroup partial sums.
     // fp32 and wide bf16 compress: this workgroup's columns [col0, col1) are part `part` of `nparts`
     // of its (row block, rank slice); with nparts > 1 the partial products live at float offset
     // `poff` of the workspace and arrivals are counted in counter `cidx`
