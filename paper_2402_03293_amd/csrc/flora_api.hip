@@ -277,9 +277,7 @@ void build_decompress_items(Plan& p)
 {
     // the 16-byte-per-lane kernel needs rows of W that start on 16-byte boundaries and 32-bit
     // lane offsets (32 m * 4 bytes below 2^31)
-    // (at r = 64 the state block is small and the narrower 4-byte kernel, with twice as many
-    // workgroups, measured faster on GPT-2-base shapes: the vector kernel is the default from r = 128)
-    int vec = rank_bf16(p.r) && (g_tune.decompress_vec < 0 ? p.r >= 128 : g_tune.decompress_vec != 0);
+    int vec = rank_bf16(p.r) && (g_tune.decompress_vec != 0);
     for (const MatDev& M : p.host_mats) vec = vec && (M.m % 4) == 0 && M.m <= (1LL << 23);
     p.vec = vec;
     const int cols = vec ? kDecompressColsVec : kDecompressCols;

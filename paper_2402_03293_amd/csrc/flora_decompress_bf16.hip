@@ -118,8 +118,10 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
 // the product is taken transposed, Gt^T = A state^T, on
 // v_mfma_f32_16x16x32_bf16, so that the accumulator of a 16 x 16 tile holds, per
 // lane, four consecutive columns of one row of W (lane % 16 = row, lane / 16 =
-// group of four columns).  W is then read and written 16 bytes per lane,
-// 16 rows x 64 contiguous bytes per instruction, instead of 4 bytes per lane.
+// group of four columns); a round trip through a staging tile in LDS that belongs
+// to the wave alone then puts eight lanes along each row, and W is read and
+// written 16 bytes per lane, 8 rows x 128 contiguous bytes (whole cache lines) per
+// instruction.
 //
 // One workgroup (8 waves) owns 256 columns and a block of rows; a wave owns 32
 // columns (two 16-wide tiles).  (The state block a workgroup fetches per 32 rows
@@ -134,8 +136,10 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
 // current block multiplies.
 template <int MODE>
 struct VecPre {
-    v4f w[(MODE == kModeSgd || MODE == kModeFactored) ? 4 : 1];   // [i-tile * 2 + j-tile]
-    float rs[(MODE == kModeRms || MODE == kModeFactored) ? 2 : 1]; // row statistic of this lane's two rows
+    v4f w[(MODE == kModeSgd || MODE == kModeFactored) ? 4 : 1];   // rows lane / 8 + 8 p, p < 4
+    // row statistics: of those four rows (kModeFactored), or of rows li and 16 + li (kModeRms,
+    // which works on the accumulator layout)
+    float rs[MODE == kModeFactored ? 4 : (MODE == kModeRms ? 2 : 1)];
 };
 
 template <int R, int MODE, typename OT>
@@ -146,9 +150,12 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     constexpr int S = R / 32;          // MFMA steps along the rank axis
     constexpr int LDS_ROW = R + 8;     // padded row (bf16 elements)
     constexpr int F4 = R / 64;         // float4 loads per thread for one 32 x R block
+    constexpr int TROW = 36;           // padded row of a wave's 32 x 32 staging tile (floats)
     constexpr bool kUsesW = (MODE == kModeSgd || MODE == kModeFactored);
-    constexpr bool kUsesRs = (MODE == kModeRms || MODE == kModeFactored);
+    // the two reduction passes move no weights: they work on the accumulators where they are
+    constexpr bool kReduce = (MODE == kModeStats || MODE == kModeRms);
     __shared__ __attribute__((aligned(16))) uint16_t ldsS[2][32][LDS_ROW];
+    __shared__ __attribute__((aligned(16))) float ldsT[kReduce ? 1 : 8][kReduce ? 1 : 32][TROW];
     __shared__ float lds_row[2][8][32];   // kModeStats: per-wave row sums of a block, double buffered
     __shared__ float lds_fin[8];
 
@@ -160,6 +167,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, g = lane >> 4;
+    const int er = lane >> 3, ec = lane & 7;     // epilogue: row er + 8 p, columns 4 ec .. 4 ec + 3
     const float cgen = neg2_ln2_over(R);
     const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
     const long long row_end = ((long long)it.row0 + it.rows < n) ? (long long)it.row0 + it.rows : n;
@@ -180,38 +188,51 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         }
     }
 
-    // Output coordinates of this lane: row = block row + 16 * i-tile + li, columns
-    // c0[jt] .. c0[jt] + 3; m % 4 == 0, so the four columns are all in or all out.
-    uint32_t c0[2];
-    bool cok[2];
+    // The accumulator of a 16 x 16 tile holds, per lane, four consecutive columns of one row;
+    // the wave's 32 x 32 block then goes through its own staging tile in LDS and comes back
+    // with eight lanes along each row: lane (er, ec) holds columns 4 ec .. 4 ec + 3 of rows
+    // er + 8 p.  A row of the block is one 128-byte line of W, so every load and store
+    // instruction moves whole lines (8 rows x 128 bytes), the cheapest pattern for the
+    // texture path.  m % 4 == 0: the four columns are all in or all out.
+    const uint32_t c0 = (uint32_t)it.col0 + 32u * wave + 4u * ec;
+    const bool cok = c0 < (uint32_t)m;
+
+    // the same for the accumulator layout (reduction passes): columns d0[jt] .. d0[jt] + 3
+    uint32_t d0[2];
+    bool dok[2];
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt) {
-        c0[jt] = (uint32_t)it.col0 + 32u * wave + 16u * jt + 4u * g;
-        cok[jt] = c0[jt] < (uint32_t)m;
+        d0[jt] = (uint32_t)it.col0 + 32u * wave + 16u * jt + 4u * g;
+        dok[jt] = d0[jt] < (uint32_t)m;
     }
 
     // per-column factors (kModeRms / kModeFactored) and running column sums (kModeStats)
-    float kfac[2][4], colsum[2][4];
+    float kfac[4], colsum[4];          // row-contiguous layout
+    float kfacd[2][4], colsumd[2][4];  // accumulator layout
     float total = 0.f;
 #pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
+    for (int v = 0; v < 4; ++v) {
+        kfac[v] = 0.f;
+        colsum[v] = 0.f;
+        kfacd[0][v] = kfacd[1][v] = 0.f;
+        colsumd[0][v] = colsumd[1][v] = 0.f;
+    }
+    if (MODE == kModeFactored) {
+        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            kfac[jt][v] = 0.f;
-            colsum[jt][v] = 0.f;
+            if (!cok) continue;
+            // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
+            kfac[v] = p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + c0 + v));
         }
-    if (MODE == kModeFactored || MODE == kModeRms) {
-        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
+    }
+    if (MODE == kModeRms) {
+        const float meanR = ldg(M.scal);
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (!cok[jt]) continue;
-                const float K = ldg(M.col_stat + c0[jt] + v);
-                // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
-                kfac[jt][v] = (MODE == kModeFactored) ? p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(K)
-                                                      : p.alpha * p.alpha * meanR / K;
-            }
+            for (int v = 0; v < 4; ++v)
+                if (dok[jt]) kfacd[jt][v] = p.alpha * p.alpha * meanR / ldg(M.col_stat + d0[jt] + v);
     }
 
     // cooperative fetch of a 32 x R block of the state: float4 number f = tid + 512 i
@@ -244,18 +265,24 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         if (MODE == kModeOut) return make_rsrc(reinterpret_cast<OT*>(M.out) + base * m, rows * m * (long long)sizeof(OT));
         return make_rsrc(M.weight + base * m, rows * m * 4);
     };
-    auto woff = [&](int itile, int jt) -> uint32_t {
-        return cok[jt] ? ((uint32_t)(16 * itile + li) * (uint32_t)m + c0[jt]) * (uint32_t)sizeof(OT) : kOob;
+    auto woff = [&](int pp) -> uint32_t {
+        return cok ? ((uint32_t)(er + 8 * pp) * (uint32_t)m + c0) * (uint32_t)sizeof(OT) : kOob;
     };
     auto pre_fetch = [&](VecPre<MODE>& pre, long long rb) {
         if (kUsesW) {
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
-            for (int itile = 0; itile < 2; ++itile)
-#pragma unroll
-                for (int jt = 0; jt < 2; ++jt) pre.w[itile * 2 + jt] = buf_load_f4(rw, woff(itile, jt));
+            for (int pp = 0; pp < 4; ++pp) pre.w[pp] = buf_load_f4(rw, woff(pp));
         }
-        if (kUsesRs) {
+        if (MODE == kModeFactored) {
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                long long row = rb + er + 8 * pp;
+                if (row > n - 1) row = n - 1;
+                pre.rs[pp] = ldg(M.row_stat + row);
+            }
+        }
+        if (MODE == kModeRms) {
 #pragma unroll
             for (int itile = 0; itile < 2; ++itile) {
                 long long row = rb + 16 * itile + li;
@@ -295,50 +322,53 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
             }
         }
 
-        // ---- epilogue on the accumulators: acc[itile][jt][v] = (state A^T)[rb + 16 itile + li, c0[jt] + v]
+        // ---- accumulators -> row-contiguous layout through this wave's staging tile
+        // (acc[itile][jt][v] = (state A^T)[rb + 16 itile + li, 32 wave + 16 jt + 4 g + v])
+        v4f gt[4];                     // gt[pp] = (state A^T)[rb + er + 8 pp, c0 .. c0 + 3]
+        if (!kReduce) {
+#pragma unroll
+            for (int itile = 0; itile < 2; ++itile)
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+                    *reinterpret_cast<f32x4*>(&ldsT[wave][16 * itile + li][16 * jt + 4 * g]) = acc[itile][jt];
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) gt[pp] = *reinterpret_cast<const v4f*>(&ldsT[wave][er + 8 * pp][4 * ec]);
+        }
+
         if (MODE == kModeOut) {
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
-            for (int itile = 0; itile < 2; ++itile)
-#pragma unroll
-                for (int jt = 0; jt < 2; ++jt) {
-                    const f32x4 a4 = acc[itile][jt];
-                    if (sizeof(OT) == 4) {
-                        buf_store_f4(rw, woff(itile, jt), v4f{p.alpha * a4[0], p.alpha * a4[1], p.alpha * a4[2], p.alpha * a4[3]});
-                    } else {
-                        const v2u pk = {pack_bf16x2(p.alpha * a4[0], p.alpha * a4[1]), pack_bf16x2(p.alpha * a4[2], p.alpha * a4[3])};
-                        buf_store_u2(rw, woff(itile, jt), pk);
-                    }
+            for (int pp = 0; pp < 4; ++pp) {
+                const v4f a4 = gt[pp];
+                if (sizeof(OT) == 4) {
+                    buf_store_f4(rw, woff(pp), v4f{p.alpha * a4.x, p.alpha * a4.y, p.alpha * a4.z, p.alpha * a4.w});
+                } else {
+                    const v2u pk = {pack_bf16x2(p.alpha * a4.x, p.alpha * a4.y), pack_bf16x2(p.alpha * a4.z, p.alpha * a4.w)};
+                    buf_store_u2(rw, woff(pp), pk);
                 }
+            }
         } else if (MODE == kModeSgd) {
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
-            for (int itile = 0; itile < 2; ++itile)
-#pragma unroll
-                for (int jt = 0; jt < 2; ++jt) {
-                    const f32x4 a4 = acc[itile][jt];
-                    const v4f w = pre0.w[itile * 2 + jt];
-                    buf_store_f4(rw, woff(itile, jt), v4f{w.x - p.coef * a4[0], w.y - p.coef * a4[1],
-                                                         w.z - p.coef * a4[2], w.w - p.coef * a4[3]});
-                }
+            for (int pp = 0; pp < 4; ++pp) {
+                const v4f a4 = gt[pp], w = pre0.w[pp];
+                buf_store_f4(rw, woff(pp), v4f{w.x - p.coef * a4.x, w.y - p.coef * a4.y,
+                                               w.z - p.coef * a4.z, w.w - p.coef * a4.w});
+            }
         } else if (MODE == kModeFactored) {
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
-            for (int itile = 0; itile < 2; ++itile) {
-                const float ri = rsqrtf(pre0.rs[itile]);
-#pragma unroll
-                for (int jt = 0; jt < 2; ++jt) {
-                    const f32x4 a4 = acc[itile][jt];
-                    const v4f w = pre0.w[itile * 2 + jt];
-                    buf_store_f4(rw, woff(itile, jt), v4f{w.x - kfac[jt][0] * ri * a4[0], w.y - kfac[jt][1] * ri * a4[1],
-                                                         w.z - kfac[jt][2] * ri * a4[2], w.w - kfac[jt][3] * ri * a4[3]});
-                }
+            for (int pp = 0; pp < 4; ++pp) {
+                const float ri = rsqrtf(pre0.rs[pp]);
+                const v4f a4 = gt[pp], w = pre0.w[pp];
+                buf_store_f4(rw, woff(pp), v4f{w.x - kfac[0] * ri * a4.x, w.y - kfac[1] * ri * a4.y,
+                                               w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w});
             }
         } else if (MODE == kModeStats) {
             // squares of Gt: column sums stay in registers for the whole sweep; row sums go
             // over the four column groups of the wave, then over the eight waves through LDS
-            // (fixed order).  Rows past the end hold zeros (their state rows are clamped
-            // copies, so they must be masked) and columns past m are masked as well.
+            // (fixed order).  Rows past the end (their state rows are clamped copies) and
+            // columns past m are masked.
 #pragma unroll
             for (int itile = 0; itile < 2; ++itile) {
                 const bool rok = rb + 16 * itile + li < row_end;
@@ -347,9 +377,9 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float gt = p.alpha * acc[itile][jt][v];
-                        const float q = (rok && cok[jt]) ? gt * gt : 0.f;
-                        colsum[jt][v] += q;
+                        const float x = p.alpha * acc[itile][jt][v];
+                        const float q = (rok && dok[jt]) ? x * x : 0.f;
+                        colsumd[jt][v] += q;
                         rsum += q;
                     }
                 rsum += __shfl_xor(rsum, 16);
@@ -365,7 +395,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
-                        if (rok) total += acc[itile][jt][v] * acc[itile][jt][v] * kfac[jt][v] * rinv;
+                        if (rok) total += acc[itile][jt][v] * acc[itile][jt][v] * kfacd[jt][v] * rinv;
             }
         }
 
@@ -386,17 +416,17 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     }
 
     if (MODE == kModeStats) {
-        // column sums over the 16 rows-lanes that share a column group, then one store per column
+        // column sums over the 16 row-lanes that share a column group, then one store per column
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float c = colsum[jt][v];
+                float c = colsumd[jt][v];
                 c += __shfl_xor(c, 8);
                 c += __shfl_xor(c, 4);
                 c += __shfl_xor(c, 2);
                 c += __shfl_xor(c, 1);
-                if (li == 0 && cok[jt]) stg(M.colpart + (long long)it.rblock * m + c0[jt] + v, c);
+                if (li == 0 && dok[jt]) stg(M.colpart + (long long)it.rblock * m + d0[jt] + v, c);
             }
     }
     if (MODE == kModeRms) {
@@ -411,7 +441,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         __syncthreads();
         if (tid == 0)
             M.itempart[it.part] = ((lds_fin[0] + lds_fin[1]) + (lds_fin[2] + lds_fin[3])) +
-                                                    ((lds_fin[4] + lds_fin[5]) + (lds_fin[6] + lds_fin[7]));
+                                  ((lds_fin[4] + lds_fin[5]) + (lds_fin[6] + lds_fin[7]));
     }
 }
 
