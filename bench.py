@@ -42,6 +42,8 @@ def parse_args():
                     help="also launch the library's plain 1 GiB copy kernel 3 times (profiler yardstick)")
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the launches of every N-th timed step with HIP events")
+    ap.add_argument("--tune", default="", help="launch-shape overrides for sweeps: name=value[,name=value...] "
+                                               "(names of flora_set_tuning)")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     return ap.parse_args()
@@ -61,6 +63,10 @@ def main():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(1)
     flora.lib()                       # fail loudly if the HIP library is missing
+    for kv in args.tune.split(","):
+        if kv:
+            name, val = kv.split("=")
+            flora.set_tuning(name, int(val))
     torch.cuda.set_device(0)
     dev = "cuda:0"
     wl = workloads.workload(args.config)
