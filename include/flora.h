@@ -34,12 +34,19 @@
  *     fp32 accumulation; bf16 gradients only; A and, when decompressing, the
  *     state are rounded to bf16 on the fly).  Other r: FLORA_ERR_UNSUPPORTED.
  *   - The library keeps a private per-device workspace (descriptor tables,
- *     the r x r transfer matrices, statistic partials).  It grows on demand
+ *     the r x r transfer matrices, statistic partials, and for small launches
+ *     the partial products and arrival counters of row blocks whose columns
+ *     are shared between workgroups).  It grows on demand
  *     with hipMalloc the first time a given set of descriptors is seen and is
  *     reused afterwards; flora_shutdown() releases it.  No per-matrix state
  *     (seed, step, epoch) is kept between calls: that lives with the caller.
  *   - Calls on one stream execute in order.  Calls issued concurrently from
- *     several host threads are serialised by an internal lock.
+ *     several host threads are serialised by an internal lock.  Two calls on
+ *     the same matrices (the same grad / weight / state pointers) must not
+ *     run at the same time on different streams: they would race on the
+ *     caller's state and on the workspace kept for that set.
+ *   - Results are bitwise repeatable: every reduction has a fixed order (no
+ *     floating-point atomics), also where workgroups combine partial products.
  */
 #ifndef FLORA_H_
 #define FLORA_H_
