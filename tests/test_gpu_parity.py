@@ -246,16 +246,25 @@ def test_compress_grouped_many_matrices_and_accumulation():
         assert rel_fro(to64(states[l]), ref[l]) < TOL_F32
 
 
-def test_compress_is_bitwise_repeatable():
-    n, m, r = 300, 520, 64
-    G = rand((n, m), 9, torch.bfloat16)
+@pytest.mark.parametrize("r,gdt,kc", [(64, "bf16", 0), (256, "bf16", 128), (16, "f32", 128), (32, "bf16", 64)])
+def test_compress_is_bitwise_repeatable(r, gdt, kc):
+    # also with shared columns: whichever workgroup arrives last adds the partial products in
+    # the same order
+    n, m = 300, 1032
+    tdt = torch.float32 if gdt == "f32" else torch.bfloat16
+    fdt = flora.F32 if gdt == "f32" else flora.BF16
+    G = rand((n, m), 9, tdt)
     outs = []
-    for _ in range(3):
-        st = torch.zeros((n, r), device=DEV)
-        flora.compress(flora.matrices([(n, m)], grads=[G], states=[st], seeds=[4]), r, flora.BF16)
-        sync()
-        outs.append(st.cpu().numpy())
-    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    flora.set_tuning("compress_splitk_cols", kc)
+    try:
+        for _ in range(4):
+            st = torch.zeros((n, r), device=DEV)
+            flora.compress(flora.matrices([(n, m)], grads=[G], states=[st], seeds=[4]), r, fdt)
+            sync()
+            outs.append(st.cpu().numpy())
+    finally:
+        flora.set_tuning("compress_splitk_cols", 0)
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
 
 
 # ------------------------------------------------------------ decompress
