@@ -281,7 +281,8 @@ void build_decompress_items(Plan& p)
     for (const MatDev& M : p.host_mats) vec = vec && (M.m % 4) == 0 && M.m <= (1LL << 23);
     p.vec = vec;
     const int cols = vec ? kDecompressColsVec : kDecompressCols;
-    const int rows_per_wg = choose_decompress_rows(p.host_mats, cols);
+    // (the vector kernel addresses a workgroup's state rows with 32-bit byte offsets)
+    const int rows_per_wg = std::min(choose_decompress_rows(p.host_mats, cols), vec ? (1 << 20) : 0x7fffffe0);
     struct Group { int mat, rb, row0, rows, nchunks; };
     std::vector<Group> groups;
     for (int l = 0; l < p.count; ++l) {

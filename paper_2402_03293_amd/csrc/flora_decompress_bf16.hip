@@ -236,15 +236,20 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     }
 
     // cooperative fetch of a 32 x R block of the state: float4 number f = tid + 512 i
-    // covers row f / (R/4), columns 4 (f % (R/4)) .. +3
-    auto fetch = [&](v4f (&dst)[F4], long long rb) {
+    // covers row f / (R/4), columns 4 (f % (R/4)) .. +3.  The buffer resource covers exactly
+    // this workgroup's rows: rows past them read as zero, so Gt is zero there and neither the
+    // statistics nor the stores need a row mask (32-bit offsets: rows * R * 4 < 2^31).
+    const rsrc_t srs = make_rsrc(state + (long long)it.row0 * R, (row_end - it.row0) * (long long)R * 4);
+    uint32_t soff[F4];
 #pragma unroll
-        for (int i = 0; i < F4; ++i) {
-            const int f = tid + 512 * i;
-            long long row = rb + f / (R / 4);
-            if (row > n - 1) row = n - 1;
-            dst[i] = ldg4(state + row * R + 4 * (f % (R / 4)));
-        }
+    for (int i = 0; i < F4; ++i) {
+        const int f = tid + 512 * i;
+        soff[i] = ((uint32_t)(f / (R / 4)) * R + 4u * (uint32_t)(f % (R / 4))) * 4u;
+    }
+    auto fetch = [&](v4f (&dst)[F4], long long rb) {
+        const uint32_t boff = (uint32_t)(rb - it.row0) * (uint32_t)(R * 4);
+#pragma unroll
+        for (int i = 0; i < F4; ++i) dst[i] = buf_load_f4(srs, boff + soff[i]);
     };
     auto stash = [&](const v4f (&src)[F4], int buf) {
 #pragma unroll
@@ -365,37 +370,36 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                                                w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w});
             }
         } else if (MODE == kModeStats) {
-            // squares of Gt: column sums stay in registers for the whole sweep; row sums go
-            // over the four column groups of the wave, then over the eight waves through LDS
-            // (fixed order).  Rows past the end (their state rows are clamped copies) and
-            // columns past m are masked.
+            // squares of state A^T (alpha^2 is applied to the sums at the end): column sums
+            // stay in registers for the whole sweep; row sums go over the four column groups
+            // of the wave, then over the eight waves through LDS (fixed order).  Rows past the
+            // end are zero already; columns past m (their A is a clamped copy) are masked.
 #pragma unroll
             for (int itile = 0; itile < 2; ++itile) {
-                const bool rok = rb + 16 * itile + li < row_end;
                 float rsum = 0.f;
 #pragma unroll
                 for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float x = p.alpha * acc[itile][jt][v];
-                        const float q = (rok && dok[jt]) ? x * x : 0.f;
-                        colsumd[jt][v] += q;
-                        rsum += q;
+                        const float x = dok[jt] ? acc[itile][jt][v] : 0.f;
+                        colsumd[jt][v] = __builtin_fmaf(x, x, colsumd[jt][v]);
+                        rsum = __builtin_fmaf(x, x, rsum);
                     }
                 rsum += __shfl_xor(rsum, 16);
                 rsum += __shfl_xor(rsum, 32);
-                if (g == 0) lds_row[buf][wave][16 * itile + li] = rsum;
+                if (g == 0) lds_row[buf][wave][16 * itile + li] = p.alpha * p.alpha * rsum;
             }
         } else if (MODE == kModeRms) {
+            // sum of U^2 = Gt^2 mean(R) / (R_i K_j): per row the K-weighted sum first, then 1 / R_i
+            // (rows past the end are zero; kfacd is zero for columns past m)
 #pragma unroll
             for (int itile = 0; itile < 2; ++itile) {
-                const bool rok = rb + 16 * itile + li < row_end;
-                const float rinv = 1.f / pre0.rs[itile];
+                float t = 0.f;
 #pragma unroll
                 for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (rok) total += acc[itile][jt][v] * acc[itile][jt][v] * kfacd[jt][v] * rinv;
+                    for (int v = 0; v < 4; ++v) t = __builtin_fmaf(acc[itile][jt][v] * acc[itile][jt][v], kfacd[jt][v], t);
+                total = __builtin_fmaf(t, 1.f / pre0.rs[itile], total);
             }
         }
 
@@ -426,7 +430,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 c += __shfl_xor(c, 4);
                 c += __shfl_xor(c, 2);
                 c += __shfl_xor(c, 1);
-                if (li == 0 && dok[jt]) stg(M.colpart + (long long)it.rblock * m + d0[jt] + v, c);
+                if (li == 0 && dok[jt]) stg(M.colpart + (long long)it.rblock * m + d0[jt] + v, p.alpha * p.alpha * c);
             }
     }
     if (MODE == kModeRms) {
