@@ -251,7 +251,7 @@ def main():
     print(json.dumps(out))
 
 
-def cpu_baseline(wl, grad_sets, W, budget_gflop):
+def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
     """The fp64 oracle, as it stands, timed on this host over a bounded sample of the same
     workload: whole matrices taken in order until the flop budget is used (at least one)."""
     import numpy as np
@@ -279,36 +279,41 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop):
     spent = 0.0
     nbytes = 0
     gb = 4 if wl.grad_dtype == "f32" else 2
-    for l in chosen:
-        n, m = wl.shapes[l]
-        seed = oracle.derive_seed(99, l, 0)
-        Wl = to64(W[l])
-        if wl.algorithm == 1:
-            C = np.zeros((n, r))
-            for i in range(wl.tau):
-                G = to64(grad_sets[i % len(grad_sets)][l])
+    # the sample is repeated until about ten seconds of oracle time have been measured
+    # (small workloads would otherwise be timed over a fraction of a second)
+    reps = 0
+    while reps == 0 or (spent < min_seconds and reps < 200):
+        reps += 1
+        for l in chosen:
+            n, m = wl.shapes[l]
+            seed = oracle.derive_seed(99, l, reps)
+            Wl = to64(W[l])
+            if wl.algorithm == 1:
+                C = np.zeros((n, r))
+                for i in range(wl.tau):
+                    G = to64(grad_sets[i % len(grad_sets)][l])
+                    t0 = time.perf_counter()
+                    C = oracle.compress(G, r, seed, state=C)
+                    spent += time.perf_counter() - t0
+                    nbytes += n * m * gb
                 t0 = time.perf_counter()
-                C = oracle.compress(G, r, seed, state=C)
+                Gt = oracle.decompress(C, m, seed, alpha=1.0 / wl.tau)
+                if wl.rule == "sgd":
+                    oracle.sgd(Wl, Gt, wl.lr)
+                else:
+                    ex = wl.extra
+                    oracle.factored_update(Wl, Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"],
+                                           ex["clip_d"], wl.lr)
+                spent += time.perf_counter() - t0
+            else:
+                G = to64(grad_sets[0][l])
+                M = np.zeros((n, r))
+                t0 = time.perf_counter()
+                M = oracle.compress(G, r, seed, state=M, a=wl.beta, b=1.0 - wl.beta)
+                Gt = oracle.decompress(M, m, seed)
+                oracle.sgd(Wl, Gt, wl.lr)
                 spent += time.perf_counter() - t0
                 nbytes += n * m * gb
-            t0 = time.perf_counter()
-            Gt = oracle.decompress(C, m, seed, alpha=1.0 / wl.tau)
-            if wl.rule == "sgd":
-                oracle.sgd(Wl, Gt, wl.lr)
-            else:
-                ex = wl.extra
-                oracle.factored_update(Wl, Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"],
-                                       ex["clip_d"], wl.lr)
-            spent += time.perf_counter() - t0
-        else:
-            G = to64(grad_sets[0][l])
-            M = np.zeros((n, r))
-            t0 = time.perf_counter()
-            M = oracle.compress(G, r, seed, state=M, a=wl.beta, b=1.0 - wl.beta)
-            Gt = oracle.decompress(M, m, seed)
-            oracle.sgd(Wl, Gt, wl.lr)
-            spent += time.perf_counter() - t0
-            nbytes += n * m * gb
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -317,9 +322,9 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop):
     threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
     return {
         "value": nbytes / spent / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-        "sample": "%d of %d matrices, whole %s, %.1f fp64 GFLOP, %.2f s of oracle calls"
+        "sample": "%d of %d matrices, whole %s, %d time(s) over: %.1f fp64 GFLOP, %.2f s of oracle calls"
                   % (len(chosen), len(wl.shapes),
-                     "accumulation cycle" if wl.algorithm == 1 else "optimizer step", fl, spent),
+                     "accumulation cycle" if wl.algorithm == 1 else "optimizer step", reps, fl * reps, spent),
     }
 
 
