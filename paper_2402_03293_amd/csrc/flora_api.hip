@@ -158,7 +158,8 @@ void build_compress_bf16_items(Plan& p)
     // Unaligned sets take the narrow kernel with the largest rows-per-workgroup (128 * mt)
     // that still gives the chip two workgroups per compute unit.
     bool aligned = true;
-    for (int l = 0; l < p.count; ++l) aligned = aligned && (p.host_mats[l].m % 8) == 0;
+    for (int l = 0; l < p.count; ++l)   // 16-byte aligned rows, 32-bit byte offsets within 64 rows
+        aligned = aligned && (p.host_mats[l].m % 8) == 0 && p.host_mats[l].m <= (1LL << 23);
     const int wide_slice = (p.r == 64) ? 64 : 128;
     auto wide_wgs = [&](int rows, long long kc) {
         long long wgs = 0;
