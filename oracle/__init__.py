@@ -74,6 +74,13 @@ def lib():
         L.fo_factored_update.argtypes = [_c_dp, _c_dp, _i64, _i64, _c_dp, _c_dp,
                                          _f64, _f64, _f64, _f64]
         L.fo_factored_update.restype = ctypes.c_int
+        L.fo_adafactor_schedule.argtypes = [_i64, _c_dp, _c_dp]
+        L.fo_adafactor_schedule.restype = None
+        L.fo_rms.argtypes = [_c_dp, _i64]
+        L.fo_rms.restype = _f64
+        L.fo_adafactor_step.argtypes = [_c_dp, _c_dp, _i64, _i64, _c_dp, _c_dp, _c_dp, ctypes.c_int,
+                                        _f64, _f64, _f64, _f64, _f64, ctypes.c_int]
+        L.fo_adafactor_step.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -202,6 +209,41 @@ def factored_update(W, Gt, R, K, beta2: float, eps1: float, clip_d: float, lr: f
     return W, R, K
 
 
+def adafactor_schedule(t: int):
+    """(rho_t, beta2_t) for step t = 1, 2, ..."""
+    rho, beta2 = _f64(0.0), _f64(0.0)
+    lib().fo_adafactor_schedule(int(t), ctypes.byref(rho), ctypes.byref(beta2))
+    return rho.value, beta2.value
+
+
+def rms(X) -> float:
+    X = _f64c(X)
+    return float(lib().fo_rms(_d(X), X.size))
+
+
+def adafactor_step(W, Gt, *, R=None, K=None, V=None, beta2: float, eps1: float = 1e-30,
+                   eps2: float = 1e-3, clip_d: float = 1.0, step: float,
+                   scale_parameter: bool = True):
+    """One Adafactor step on one matrix.  Factored when R and K are given
+    (returns (W, R, K)); unfactored when V is given (returns (W, V))."""
+    W = _f64c(W).copy()
+    Gt = _f64c(Gt)
+    n, m = W.shape
+    factored = V is None
+    if factored:
+        R = _f64c(R).copy()
+        K = _f64c(K).copy()
+        Vc = np.zeros(1)
+    else:
+        Vc = _f64c(V).copy()
+        R = np.zeros(1)
+        K = np.zeros(1)
+    if lib().fo_adafactor_step(_d(W), _d(Gt), n, m, _d(R), _d(K), _d(Vc), int(factored), beta2, eps1,
+                               eps2, clip_d, step, int(bool(scale_parameter))) != 0:
+        raise MemoryError
+    return (W, R, K) if factored else (W, Vc)
+
+
 # --------------------------------------------------------------------------
 # drivers
 # --------------------------------------------------------------------------
@@ -233,6 +275,16 @@ def algorithm1_cycle(W_list, grads_per_step, r: int, global_seed: int, epoch: in
                                          factored["beta2"], factored["eps1"],
                                          factored["clip_d"], lr)
             factored["R"][l], factored["K"][l] = Rn, Kn
+        elif rule == "adafactor":
+            # the whole Adafactor step; factored = dict(R=[..], K=[..]) or dict(V=[..]) plus
+            # beta2, eps1, eps2, clip_d, step, scale_parameter
+            f = factored
+            kw = dict(beta2=f["beta2"], eps1=f["eps1"], eps2=f["eps2"], clip_d=f["clip_d"],
+                      step=f["step"], scale_parameter=f["scale_parameter"])
+            if "V" in f:
+                Wn, f["V"][l] = adafactor_step(W, Gt, V=f["V"][l], **kw)
+            else:
+                Wn, f["R"][l], f["K"][l] = adafactor_step(W, Gt, R=f["R"][l], K=f["K"][l], **kw)
         else:
             raise ValueError(rule)
         W_out.append(Wn)

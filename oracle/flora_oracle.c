@@ -25,9 +25,11 @@
  *   - "an independent random seed" (Algorithm 1 init; Algorithm 2 resample
  *     branch) is derived from (global seed, matrix id, epoch) by one Philox
  *     call in a separate counter domain.
- *   - the factored second-moment rule is the published Adafactor algorithm
- *     (Shazeer & Stern 2018) without relative step size or parameter scaling;
- *     the paper only names Adafactor as its base optimizer (Section 3.1).
+ *   - the factored second-moment rule (fo_factored_update) is the published
+ *     Adafactor algorithm (Shazeer & Stern 2018) without relative step size or
+ *     parameter scaling; fo_adafactor_step adds those and the unfactored
+ *     second moment; the paper only names Adafactor as its base optimizer
+ *     (Section 3.1) and its unfactored variant (Section 3.3).
  *
  * All loops are the defining sums, in index order.  The only parallelism is
  * an OpenMP "parallel for" over independent output rows.
@@ -314,6 +316,89 @@ int fo_factored_update(double* W, const double* Gt, int64_t n, int64_t m,
         scale = 1.0 / (d > 1.0 ? d : 1.0);
     }
     for (int64_t i = 0; i < n * m; ++i) W[i] -= lr * scale * U[i];
+    free(U);
+    return 0;
+}
+
+/* ---- The whole Adafactor step around the decompressed gradient --------------
+ * The paper names Adafactor as the base optimizer of every headline run
+ * (Section 3.1, "Competing methods") and, in "Optimizer with linear memory"
+ * (Section 3.3), a variant whose second moment is not factored.  It gives no
+ * formulas, so these follow the published algorithm (Shazeer & Stern 2018:
+ * Algorithm 4 for matrices, Algorithm 5's elementwise second moment for the
+ * unfactored variant, Section 9 for the schedules).  Parity with the paper's
+ * own runs is UNPINNED; the functions are pinned to closed forms, special
+ * cases and invariances instead. */
+
+/* Proposed schedules for step t = 1, 2, ...: relative step size
+ * rho_t = min(1e-2, 1/sqrt(t)) and second-moment decay beta2_t = 1 - t^-0.8
+ * (so beta2_1 = 0: the first step uses the plain means). */
+void fo_adafactor_schedule(int64_t t, double* rho, double* beta2)
+{
+    const double tt = (double)t;
+    const double inv = 1.0 / sqrt(tt);
+    *rho = inv < 1e-2 ? inv : 1e-2;
+    *beta2 = 1.0 - pow(tt, -0.8);
+}
+
+/* Root mean square of `count` values. */
+double fo_rms(const double* X, int64_t count)
+{
+    double s = 0.0;
+    for (int64_t i = 0; i < count; ++i) s += X[i] * X[i];
+    return sqrt(s / (double)count);
+}
+
+/* One step on one matrix, in the published order:
+ *   alpha = step * max(eps2, RMS(W))        if scale_parameter, else alpha = step
+ *   factored:    R, K, V_ij = R_i K_j / mean(R) exactly as fo_factored_update
+ *   unfactored:  V <- beta2 V + (1 - beta2) (Gt.^2 + eps1)      (n x m, kept by the caller)
+ *   U = Gt / sqrt(V);  if clip_d > 0: U <- U / max(1, RMS(U) / clip_d);  W <- W - alpha U
+ * `step` is the relative step size rho_t when scale_parameter is set and an
+ * absolute learning rate otherwise.  R, K are used only when factored != 0,
+ * V only when factored == 0. */
+int fo_adafactor_step(double* W, const double* Gt, int64_t n, int64_t m,
+                      double* R, double* K, double* V, int factored,
+                      double beta2, double eps1, double eps2, double clip_d,
+                      double step, int scale_parameter)
+{
+    const int64_t nm = n * m;
+    double alpha = step;
+    if (scale_parameter) {
+        const double rmsW = fo_rms(W, nm);
+        alpha = step * (rmsW > eps2 ? rmsW : eps2);
+    }
+    double* U = (double*)malloc(sizeof(double) * (size_t)nm);
+    if (!U) return -1;
+    if (factored) {
+        for (int64_t i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int64_t j = 0; j < m; ++j) s += Gt[i * m + j] * Gt[i * m + j] + eps1;
+            R[i] = beta2 * R[i] + (1.0 - beta2) * (s / (double)m);
+        }
+        for (int64_t j = 0; j < m; ++j) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i) s += Gt[i * m + j] * Gt[i * m + j] + eps1;
+            K[j] = beta2 * K[j] + (1.0 - beta2) * (s / (double)n);
+        }
+        double meanR = 0.0;
+        for (int64_t i = 0; i < n; ++i) meanR += R[i];
+        meanR /= (double)n;
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t j = 0; j < m; ++j)
+                U[i * m + j] = Gt[i * m + j] / sqrt(R[i] * K[j] / meanR);
+    } else {
+        for (int64_t i = 0; i < nm; ++i) {
+            V[i] = beta2 * V[i] + (1.0 - beta2) * (Gt[i] * Gt[i] + eps1);
+            U[i] = Gt[i] / sqrt(V[i]);
+        }
+    }
+    double scale = 1.0;
+    if (clip_d > 0.0) {
+        const double d = fo_rms(U, nm) / clip_d;
+        scale = 1.0 / (d > 1.0 ? d : 1.0);
+    }
+    for (int64_t i = 0; i < nm; ++i) W[i] -= alpha * scale * U[i];
     free(U);
     return 0;
 }

@@ -393,3 +393,140 @@ def test_factored_constant_magnitude_gradient():
     np.testing.assert_allclose(R, c * c)
     np.testing.assert_allclose(K, c * c)
     np.testing.assert_allclose(Wn, -np.sign(Gt), rtol=1e-13)
+
+
+# ------------------------------------------------------ the whole Adafactor step
+def test_adafactor_schedules_closed_form_values():
+    # rho_t = min(1e-2, 1/sqrt(t)): flat up to t = 10^4, then 1/sqrt(t);
+    # beta2_t = 1 - t^-0.8: 0 at t = 1, 1 - 2^-4 at t = 32, 1 - 2^-8 at t = 1024
+    assert oracle.adafactor_schedule(1) == (1e-2, 0.0)
+    assert oracle.adafactor_schedule(32)[1] == pytest.approx(0.9375, rel=1e-15)
+    assert oracle.adafactor_schedule(1024)[1] == pytest.approx(1 - 2.0 ** -8, rel=1e-15)
+    assert oracle.adafactor_schedule(9999)[0] == 1e-2
+    assert oracle.adafactor_schedule(10000)[0] == pytest.approx(1e-2, rel=1e-15)
+    assert oracle.adafactor_schedule(40000)[0] == pytest.approx(5e-3, rel=1e-15)
+    assert oracle.adafactor_schedule(10 ** 6)[0] == pytest.approx(1e-3, rel=1e-15)
+    # beta2 increases towards 1 and never reaches it
+    b = [oracle.adafactor_schedule(t)[1] for t in (1, 2, 10, 100, 10 ** 4, 10 ** 8)]
+    assert all(x < y for x, y in zip(b, b[1:])) and b[-1] < 1.0
+
+
+def test_rms_of_constant_and_of_unit_vectors():
+    assert oracle.rms(np.full((3, 5), -4.0)) == pytest.approx(4.0, rel=1e-15)
+    e = np.zeros(16)
+    e[3] = 2.0
+    assert oracle.rms(e) == pytest.approx(0.5, rel=1e-15)   # sqrt(4 / 16)
+
+
+def test_unfactored_first_step_is_sign_descent_scaled_by_parameter_rms():
+    # beta2 = 0, eps1 -> 0: V = Gt^2, U = sign(Gt), RMS(U) = 1 (no clipping at d = 1);
+    # W constant = w0 has RMS |w0|, so W <- w0 - rho |w0| sign(Gt).
+    rng = np.random.default_rng(21)
+    n, m, w0, rho = 5, 8, -2.5, 0.01
+    Gt = rng.standard_normal((n, m))
+    W = np.full((n, m), w0)
+    Wn, V = oracle.adafactor_step(W, Gt, V=np.zeros((n, m)), beta2=0.0, eps1=1e-300, step=rho)
+    np.testing.assert_allclose(V, Gt ** 2, rtol=1e-12)
+    np.testing.assert_allclose(Wn, w0 - rho * abs(w0) * np.sign(Gt), rtol=1e-12)
+    # clipping threshold 0.5 halves the step, 2.0 leaves it
+    Wh, _ = oracle.adafactor_step(W, Gt, V=np.zeros((n, m)), beta2=0.0, eps1=1e-300, step=rho, clip_d=0.5)
+    np.testing.assert_allclose(Wh, w0 - 0.5 * rho * abs(w0) * np.sign(Gt), rtol=1e-12)
+    W2, _ = oracle.adafactor_step(W, Gt, V=np.zeros((n, m)), beta2=0.0, eps1=1e-300, step=rho, clip_d=2.0)
+    np.testing.assert_allclose(W2, Wn, rtol=1e-12)
+    # without parameter scaling `step` is an absolute learning rate
+    Wa, _ = oracle.adafactor_step(W, Gt, V=np.zeros((n, m)), beta2=0.0, eps1=1e-300, step=rho,
+                                  scale_parameter=False)
+    np.testing.assert_allclose(Wa, w0 - rho * np.sign(Gt), rtol=1e-12)
+
+
+def test_parameter_scale_floor_eps2():
+    # W = 0 has RMS 0 < eps2: the step is eps2 * rho
+    rng = np.random.default_rng(22)
+    Gt = rng.standard_normal((4, 6))
+    Wn, _ = oracle.adafactor_step(np.zeros((4, 6)), Gt, V=np.zeros((4, 6)), beta2=0.0, eps1=1e-300,
+                                  eps2=1e-3, step=0.01)
+    np.testing.assert_allclose(Wn, -1e-5 * np.sign(Gt), rtol=1e-12)
+    # just above the floor the RMS itself is used
+    W = np.full((4, 6), 2e-3)
+    Wn, _ = oracle.adafactor_step(W, Gt, V=np.zeros((4, 6)), beta2=0.0, eps1=1e-300, eps2=1e-3, step=0.01)
+    np.testing.assert_allclose(Wn, 2e-3 - 2e-5 * np.sign(Gt), rtol=1e-12)
+
+
+def test_unfactored_second_moment_is_elementwise_ema():
+    rng = np.random.default_rng(23)
+    n, m, beta2, eps1 = 3, 5, 0.7, 1e-2
+    Gt = rng.standard_normal((n, m))
+    V0 = rng.random((n, m)) + 0.5
+    W = rng.standard_normal((n, m))
+    Wn, V = oracle.adafactor_step(W, Gt, V=V0, beta2=beta2, eps1=eps1, step=0.3, clip_d=0.0,
+                                  scale_parameter=False)
+    for i in range(n):
+        for j in range(m):
+            v = 0.7 * V0[i, j] + 0.3 * (Gt[i, j] * Gt[i, j] + 1e-2)
+            assert V[i, j] == pytest.approx(v, rel=1e-13)
+            assert Wn[i, j] == pytest.approx(W[i, j] - 0.3 * Gt[i, j] / math.sqrt(v), rel=1e-12)
+
+
+def test_factored_equals_unfactored_while_second_moment_stays_rank_one():
+    # Gt_t = s_t u v^T: every Gt_t^2 lies on one rank-one ray, so the row/column factors
+    # reproduce the elementwise EMA exactly (eps1 = 0) and both variants walk the same path.
+    rng = np.random.default_rng(24)
+    n, m = 5, 7
+    u, v = rng.standard_normal(n), rng.standard_normal(m)
+    Wf = Wu = rng.standard_normal((n, m))
+    R, K, V = np.zeros(n), np.zeros(m), np.zeros((n, m))
+    for t in range(1, 6):
+        rho, beta2 = oracle.adafactor_schedule(t)
+        Gt = rng.standard_normal() * np.outer(u, v)
+        Wf, R, K = oracle.adafactor_step(Wf, Gt, R=R, K=K, beta2=beta2, eps1=0.0, step=rho)
+        Wu, V = oracle.adafactor_step(Wu, Gt, V=V, beta2=beta2, eps1=0.0, step=rho)
+        np.testing.assert_allclose(np.outer(R, K) / R.mean(), V, rtol=1e-12)
+        np.testing.assert_allclose(Wf, Wu, rtol=1e-11, atol=1e-14)
+
+
+def test_factored_estimate_in_row_sum_form():
+    # the published form keeps row SUMS R and column SUMS C and uses R C^T / (1^T R);
+    # the means kept here give the same estimate
+    rng = np.random.default_rng(25)
+    n, m, eps1 = 4, 9, 1e-4
+    Gt = rng.standard_normal((n, m))
+    W = rng.standard_normal((n, m))
+    Wn, R, K = oracle.adafactor_step(W, Gt, R=np.zeros(n), K=np.zeros(m), beta2=0.0, eps1=eps1,
+                                     step=0.1, clip_d=0.0, scale_parameter=False)
+    Q = Gt ** 2 + eps1
+    Rs, Cs = Q.sum(axis=1), Q.sum(axis=0)
+    Vhat = np.outer(Rs, Cs) / Rs.sum()
+    np.testing.assert_allclose(Wn, W - 0.1 * Gt / np.sqrt(Vhat), rtol=1e-12)
+
+
+@pytest.mark.parametrize("factored", [True, False])
+def test_relative_step_makes_the_path_scale_with_the_parameters(factored):
+    # With parameter scaling and a negligible eps1 the update direction ignores the gradient's
+    # scale and the step follows RMS(W): starting from c W0 with gradients g Gt_t gives c W_t.
+    rng = np.random.default_rng(26)
+    n, m, c, g = 6, 5, 7.0, 0.3
+    W0 = rng.standard_normal((n, m))
+    grads = [rng.standard_normal((n, m)) for _ in range(4)]
+
+    def run(W, gs):
+        st = dict(R=np.zeros(n), K=np.zeros(m)) if factored else dict(V=np.zeros((n, m)))
+        for t, Gt in enumerate(gs, start=1):
+            rho, beta2 = oracle.adafactor_schedule(t)
+            out = oracle.adafactor_step(W, Gt, beta2=beta2, eps1=0.0, eps2=1e-12, step=rho, **st)
+            W = out[0]
+            st = dict(R=out[1], K=out[2]) if factored else dict(V=out[1])
+        return W
+
+    np.testing.assert_allclose(run(c * W0, [g * G for G in grads]), c * run(W0, grads), rtol=1e-11)
+
+
+def test_adafactor_step_without_scaling_is_the_factored_rule():
+    rng = np.random.default_rng(27)
+    n, m = 7, 4
+    W, Gt = rng.standard_normal((n, m)), rng.standard_normal((n, m))
+    R0, K0 = rng.random(n) + 0.1, rng.random(m) + 0.1
+    a = oracle.factored_update(W, Gt, R0, K0, 0.6, 1e-8, 1.0, 0.02)
+    b = oracle.adafactor_step(W, Gt, R=R0, K=K0, beta2=0.6, eps1=1e-8, clip_d=1.0, step=0.02,
+                              scale_parameter=False)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
