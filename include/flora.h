@@ -80,19 +80,24 @@ typedef struct flora_matrix {
     int64_t     m;         /* columns of G and W = the compressed axis = rows of A                       */
     uint64_t    seed;      /* seed s_W of the current projection                                         */
     uint64_t    seed_next; /* seed of the projection to move to (flora_momentum_transfer, fused step)    */
+    float*      second_moment; /* device, n x m fp32: unfactored rule's second moment V, else NULL       */
+    float*      weight_sumsq;  /* device, 1 float: sum of W^2 over the matrix (parameter scale), else NULL */
 } flora_matrix_t;
 
-typedef enum { FLORA_RULE_SGD = 0, FLORA_RULE_FACTORED = 1 } flora_rule_t;
+typedef enum { FLORA_RULE_SGD = 0, FLORA_RULE_FACTORED = 1, FLORA_RULE_UNFACTORED = 2 } flora_rule_t;
 
 /* How the decompressed gradient Gt = alpha * state A^T is applied to W. */
 typedef struct flora_update {
     int   rule;              /* flora_rule_t                                                            */
     float lr;                /* learning rate eta                                                       */
     float alpha;             /* 1/tau for Algorithm 1 (arithmetic mean over the cycle), 1 for Alg. 2    */
-    float beta2;             /* factored rule: decay of R and K (0 = plain means of this step)          */
-    float eps1;              /* factored rule: added to Gt^2                                            */
-    float clip_d;            /* factored rule: RMS clipping threshold, 0 = no clipping                  */
+    float beta2;             /* Adafactor rules: decay of the second moment (0 = this step's alone)     */
+    float eps1;              /* Adafactor rules: added to Gt^2                                          */
+    float clip_d;            /* Adafactor rules: RMS clipping threshold, 0 = no clipping                */
     int   zero_state_after;  /* non-zero: state <- 0 once the update has read it (end of an Alg. 1 cycle) */
+    int   scale_parameter;   /* Adafactor rules, non-zero: the step is lr * max(eps2, RMS(W)), lr then
+                                being the relative step size rho_t; ignored by FLORA_RULE_SGD           */
+    float eps2;              /* floor of the parameter scale RMS(W)                                     */
 } flora_update_t;
 
 /* Compression (Algorithm 1, compression line: a = b = 1;  Algorithm 2, EMA
@@ -119,12 +124,23 @@ int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* 
 
 /* Decompression fused with the base optimizer's update; Gt is never stored:
  *   FLORA_RULE_SGD:       W <- W - lr * Gt            (Section 2.2, update rule)
- *   FLORA_RULE_FACTORED:  the Adafactor factored second-moment rule the paper's
- *                         experiments use as base optimizer (Section 3.1):
+ *   FLORA_RULE_FACTORED:  Adafactor, the base optimizer of the paper's experiments
+ *                         (Section 3.1), with its factored second moment:
  *       Q = Gt^2 + eps1;  R <- beta2 R + (1-beta2) rowmean(Q);  K likewise by column;
- *       U = Gt / sqrt(R_i K_j / mean(R));  U <- U / max(1, RMS(U)/clip_d);  W <- W - lr U
+ *       U = Gt / sqrt(R_i K_j / mean(R));  U <- U / max(1, RMS(U)/clip_d);  W <- W - step U
  *     (Gt is regenerated for each pass; row_stat and col_stat are updated in place).
- * Uses weight, state, n, m, seed (+ row_stat, col_stat).  weight_dtype must be FLORA_F32. */
+ *   FLORA_RULE_UNFACTORED: the variant with an elementwise second moment (Section 3.3,
+ *                         "Optimizer with linear memory"):
+ *       V <- beta2 V + (1-beta2) (Gt^2 + eps1);  U = Gt / sqrt(V);  clipping and step as above
+ *     (second_moment is updated in place).
+ *   step = lr, or lr * max(eps2, RMS(W)) with scale_parameter: RMS(W) is taken from
+ *   weight_sumsq[0] / (n m) as it stands when the call starts.  Whenever weight_sumsq is not
+ *   NULL both Adafactor rules leave the sum of squares of the NEW weights there, so a caller
+ *   that changes W by no other means fills it once (flora_weight_sumsq) and never reads W
+ *   again for it.  lr and beta2 for step t of the published schedules:
+ *   flora_adafactor_schedule.
+ * Uses weight, state, n, m, seed (+ row_stat, col_stat | second_moment, + weight_sumsq).
+ * weight_dtype must be FLORA_F32. */
 int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
                        const flora_update_t* u, void* hip_stream);
 
@@ -135,6 +151,15 @@ int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype
 int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
                      flora_dtype_t weight_dtype, float a, float b, int do_transfer,
                      const flora_update_t* u, void* hip_stream);
+
+/* weight_sumsq[0] <- sum of W^2 for every matrix (one read of W; fixed summation order).
+ * Uses weight, weight_sumsq, n, m. */
+int flora_weight_sumsq(const flora_matrix_t* mats, int count, void* hip_stream);
+
+/* Host-side helper: Adafactor's published schedules for step t = 1, 2, ... (t = 0 is read
+ * as 1): relative step size *rho = min(1e-2, 1/sqrt(t)) and second-moment decay
+ * *beta2 = 1 - t^-0.8 (0 at t = 1).  Either pointer may be NULL.  Never fails. */
+void flora_adafactor_schedule(uint64_t t, float* rho, float* beta2);
 
 /* Test hook: writes A(seed) (m x r fp32, row-major) to A_out and/or the raw
  * Philox words (m x ceil(r/4) x 4 uint32) to raw_out; either may be NULL.

@@ -8,6 +8,7 @@
 #include "flora_internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -33,7 +34,8 @@ enum Kind : int {
     kKindCompress = 0,
     kKindDecompress = 1,   // also SGD update: needs only the decompress table
     kKindTransfer = 2,
-    kKindFactored = 3
+    kKindFactored = 3,     // the Adafactor rules: statistic partials, per-workgroup sums, scalars
+    kKindSumsq = 4         // sum of W^2 from scratch
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -354,6 +356,7 @@ size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r)
             b += round_up((size_t)M.nitems * 4, 256);
             b += 256;
         }
+        if (kind == kKindSumsq) b += (size_t)kSumsqBlocks * 4;
     }
     return b;
 }
@@ -369,7 +372,7 @@ Match compare(const Plan& p, const std::vector<MatDev>& mats)
         const MatDev& b = mats[l];
         if (a.n != b.n || a.m != b.m) return kShapesDiffer;
         if (a.grad != b.grad || a.weight != b.weight || a.state != b.state || a.row_stat != b.row_stat ||
-            a.col_stat != b.col_stat || a.out != b.out)
+            a.col_stat != b.col_stat || a.out != b.out || a.vfull != b.vfull || a.wsumsq != b.wsumsq)
             worst = kPointersDiffer;
         else if (worst < kSeedsDiffer && (a.seed_lo != b.seed_lo || a.seed_hi != b.seed_hi ||
                                           a.seedn_lo != b.seedn_lo || a.seedn_hi != b.seedn_hi))
@@ -445,7 +448,7 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
         if (kind == kKindCompress) {
             if (variant == 2) build_compress_bf16_items(*p);
             else build_compress_f32_items(*p);
-        } else {
+        } else if (kind != kKindSumsq) {
             build_decompress_items(*p);
             if (kind == kKindTransfer) build_apply_T_items(*p);
         }
@@ -632,39 +635,69 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, hipStrea
 static int update_chunk(const flora_matrix_t* mats, int count, int r, const flora_update_t* u, bool use_next,
                         hipStream_t s)
 {
+    const bool factored = u->rule == FLORA_RULE_FACTORED, unfactored = u->rule == FLORA_RULE_UNFACTORED;
+    const bool scaled = (factored || unfactored) && u->scale_parameter != 0;
     std::vector<MatDev> md((size_t)count);
+    bool any_sumsq = false;
     for (int l = 0; l < count; ++l) {
         MatDev M{};
         M.weight = static_cast<float*>(mats[l].weight); M.state = mats[l].state;
         M.n = mats[l].n; M.m = mats[l].m;
-        if (u->rule == FLORA_RULE_FACTORED) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
+        if (factored) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
+        if (unfactored) M.vfull = mats[l].second_moment;
+        if (factored || unfactored) M.wsumsq = mats[l].weight_sumsq;
+        any_sumsq = any_sumsq || M.wsumsq != nullptr;
         md[(size_t)l] = M;
     }
     SeedArgs sa;
     fill_seed_args(sa, mats, count, use_next);
     Plan* p = nullptr;
-    const int kind = (u->rule == FLORA_RULE_FACTORED) ? kKindFactored : kKindDecompress;
-    int st = get_plan(kind, 2, r, md, s, &p);
+    const int kind = (factored || unfactored) ? kKindFactored : kKindDecompress;
+    int st = get_plan(kind, unfactored ? 3 : 2, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     if (u->rule == FLORA_RULE_SGD) {
-        DecompressParams dp{u->alpha, u->lr * u->alpha};
+        DecompressParams dp{u->alpha, u->lr * u->alpha, 0.f, 0.f};
         st = run_decompress(p, sa, r, kModeSgd, 0, dp, s);
         if (st != FLORA_OK) return st;
     } else {
-        DecompressParams dp{u->alpha, u->lr};
-        st = run_decompress(p, sa, r, kModeStats, 0, dp, s);
-        if (st != FLORA_OK) return st;
-        FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
-        if (u->clip_d > 0.f) {
-            st = run_decompress(p, sa, r, kModeRms, 0, dp, s);
+        DecompressParams dp{u->alpha, u->lr, u->beta2, u->eps1};
+        if (factored) {
+            st = run_decompress(p, sa, r, kModeStats, 0, dp, s);
             if (st != FLORA_OK) return st;
-            FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, s));
+            FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
+            if (u->clip_d > 0.f) {
+                st = run_decompress(p, sa, r, kModeRms, 0, dp, s);
+                if (st != FLORA_OK) return st;
+            }
+        } else {
+            st = run_decompress(p, sa, r, kModeFull1, 0, dp, s);
+            if (st != FLORA_OK) return st;
         }
-        st = run_decompress(p, sa, r, kModeFactored, 0, dp, s);
+        // clip factor from the partial sums of U^2; parameter scale from the caller's sum of W^2
+        FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, scaled ? 1 : 0, u->eps2, s));
+        st = run_decompress(p, sa, r, factored ? kModeFactored : kModeFull2, 0, dp, s);
         if (st != FLORA_OK) return st;
+        // the update pass left per-workgroup sums of the new W^2
+        if (any_sumsq) FLORA_HIP(launch_wsumsq_finalize(dm, count, s));
     }
     if (u->zero_state_after) FLORA_HIP(launch_zero_state(dm, count, r, s));
+    return FLORA_OK;
+}
+
+static int sumsq_chunk(const flora_matrix_t* mats, int count, hipStream_t s)
+{
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) {
+        MatDev M{};
+        M.weight = static_cast<float*>(mats[l].weight); M.wsumsq = mats[l].weight_sumsq;
+        M.n = mats[l].n; M.m = mats[l].m;
+        md[(size_t)l] = M;
+    }
+    Plan* p = nullptr;
+    int st = get_plan(kKindSumsq, 0, 0, md, s, &p);
+    if (st != FLORA_OK) return st;
+    FLORA_HIP(launch_weight_sumsq(static_cast<const MatDev*>(p->d_table), count, static_cast<float*>(p->d_work), s));
     return FLORA_OK;
 }
 
@@ -686,15 +719,24 @@ static int check_update(const flora_matrix_t* mats, int count, int r, flora_dtyp
     if (st != FLORA_OK) return st;
     if (!u) return FLORA_ERR_INVALID;
     if (!dtype_ok((int)weight_dtype)) return FLORA_ERR_INVALID;
-    if (u->rule != FLORA_RULE_SGD && u->rule != FLORA_RULE_FACTORED) return FLORA_ERR_INVALID;
-    if (u->rule == FLORA_RULE_FACTORED &&
-        (!(u->beta2 >= 0.f && u->beta2 <= 1.f) || !(u->clip_d >= 0.f) || !(u->eps1 >= 0.f)))
+    if (u->rule != FLORA_RULE_SGD && u->rule != FLORA_RULE_FACTORED && u->rule != FLORA_RULE_UNFACTORED)
         return FLORA_ERR_INVALID;
+    const bool ada = u->rule != FLORA_RULE_SGD;
+    if (ada && (!(u->beta2 >= 0.f && u->beta2 <= 1.f) || !(u->clip_d >= 0.f) || !(u->eps1 >= 0.f)))
+        return FLORA_ERR_INVALID;
+    if (ada && u->scale_parameter && !(u->eps2 >= 0.f)) return FLORA_ERR_INVALID;
     for (int l = 0; l < count; ++l) {
         if (!mats[l].weight || !aligned16(mats[l].weight) || mats[l].weight == (void*)mats[l].state)
             return FLORA_ERR_INVALID;
         if (u->rule == FLORA_RULE_FACTORED &&
             (!mats[l].row_stat || !mats[l].col_stat || !aligned16(mats[l].row_stat) || !aligned16(mats[l].col_stat)))
+            return FLORA_ERR_INVALID;
+        if (u->rule == FLORA_RULE_UNFACTORED &&
+            (!mats[l].second_moment || !aligned16(mats[l].second_moment) ||
+             (void*)mats[l].second_moment == mats[l].weight || mats[l].second_moment == mats[l].state))
+            return FLORA_ERR_INVALID;
+        if (ada && u->scale_parameter && !mats[l].weight_sumsq) return FLORA_ERR_INVALID;
+        if (ada && mats[l].weight_sumsq && (reinterpret_cast<uintptr_t>(mats[l].weight_sumsq) & 3u))
             return FLORA_ERR_INVALID;
     }
     if (weight_dtype != FLORA_F32) return FLORA_ERR_UNSUPPORTED;
@@ -785,6 +827,31 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;
+}
+
+int flora_weight_sumsq(const flora_matrix_t* mats, int count, void* hip_stream)
+{
+    if (count < 0 || (count > 0 && !mats)) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l) {
+        if (mats[l].n < 1 || mats[l].m < 1) return FLORA_ERR_INVALID;
+        if (mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24)) return FLORA_ERR_INVALID;
+        if (!mats[l].weight || !aligned16(mats[l].weight)) return FLORA_ERR_INVALID;
+        if (!mats[l].weight_sumsq || (reinterpret_cast<uintptr_t>(mats[l].weight_sumsq) & 3u))
+            return FLORA_ERR_INVALID;
+    }
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        const int st = sumsq_chunk(mats + c0, cn, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
+    return FLORA_OK;
+}
+
+void flora_adafactor_schedule(uint64_t t, float* rho, float* beta2)
+{
+    const double tt = t < 1 ? 1.0 : (double)t;
+    if (rho) *rho = (float)std::min(1e-2, 1.0 / std::sqrt(tt));
+    if (beta2) *beta2 = (float)(1.0 - std::pow(tt, -0.8));
 }
 
 int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out, void* hip_stream)
@@ -895,6 +962,6 @@ void flora_shutdown(void)
     g_plans.clear();
 }
 
-int flora_version(void) { return 100; }
+int flora_version(void) { return 200; }
 
 }  // extern "C"

@@ -136,7 +136,8 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
 // current block multiplies.
 template <int MODE>
 struct VecPre {
-    v4f w[(MODE == kModeSgd || MODE == kModeFactored) ? 4 : 1];   // rows lane / 8 + 8 p, p < 4
+    v4f w[(MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2) ? 4 : 1];   // rows lane / 8 + 8 p, p < 4
+    v4f v[(MODE == kModeFull1 || MODE == kModeFull2) ? 4 : 1];    // unfactored second moment, same rows
     // row statistics: of those four rows (kModeFactored), or of rows li and 16 + li (kModeRms,
     // which works on the accumulator layout)
     float rs[MODE == kModeFactored ? 4 : (MODE == kModeRms ? 2 : 1)];
@@ -151,7 +152,10 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     constexpr int LDS_ROW = R + 8;     // padded row (bf16 elements)
     constexpr int F4 = R / 64;         // float4 loads per thread for one 32 x R block
     constexpr int TROW = 36;           // padded row of a wave's 32 x 32 staging tile (floats)
-    constexpr bool kUsesW = (MODE == kModeSgd || MODE == kModeFactored);
+    constexpr bool kUsesW = (MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2);
+    constexpr bool kUsesV = (MODE == kModeFull1 || MODE == kModeFull2);
+    // passes that end with one partial sum per workgroup (of U^2, or of the new W^2)
+    constexpr bool kTotals = (MODE == kModeRms || MODE == kModeFactored || MODE == kModeFull1 || MODE == kModeFull2);
     // the two reduction passes move no weights: they work on the accumulators where they are
     constexpr bool kReduce = (MODE == kModeStats || MODE == kModeRms);
     __shared__ __attribute__((aligned(16))) uint16_t ldsS[2][32][LDS_ROW];
@@ -218,14 +222,17 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         colsumd[0][v] = colsumd[1][v] = 0.f;
     }
     if (MODE == kModeFactored) {
-        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
+        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1), ps = ldg(M.scal + 2);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (!cok) continue;
-            // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
-            kfac[v] = p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + c0 + v));
+            // U = Gt / sqrt(R_i K_j / mean R), scaled by lr, the RMS clip factor and the
+            // parameter scale (max(eps2, RMS(W)), or 1)
+            kfac[v] = p.coef * p.alpha * clip * ps * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + c0 + v));
         }
     }
+    // kModeFull2: U = Gt / sqrt(V_ij), scaled the same way
+    const float kfull = (MODE == kModeFull2) ? p.coef * p.alpha * ldg(M.scal + 1) * ldg(M.scal + 2) : 0.f;
     if (MODE == kModeRms) {
         const float meanR = ldg(M.scal);
 #pragma unroll
@@ -270,6 +277,12 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         if (MODE == kModeOut) return make_rsrc(reinterpret_cast<OT*>(M.out) + base * m, rows * m * (long long)sizeof(OT));
         return make_rsrc(M.weight + base * m, rows * m * 4);
     };
+    auto vrsrc = [&](long long rb) -> rsrc_t {
+        long long rows = row_end - rb;
+        rows = rows < 0 ? 0 : (rows > 32 ? 32 : rows);
+        const long long base = rb < n ? rb : 0;
+        return make_rsrc(M.vfull + base * m, rows * m * 4);
+    };
     auto woff = [&](int pp) -> uint32_t {
         return cok ? ((uint32_t)(er + 8 * pp) * (uint32_t)m + c0) * (uint32_t)sizeof(OT) : kOob;
     };
@@ -278,6 +291,11 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
             for (int pp = 0; pp < 4; ++pp) pre.w[pp] = buf_load_f4(rw, woff(pp));
+        }
+        if (kUsesV) {
+            const rsrc_t rv = vrsrc(rb);
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) pre.v[pp] = buf_load_f4(rv, woff(pp));
         }
         if (MODE == kModeFactored) {
 #pragma unroll
@@ -366,8 +384,44 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
             for (int pp = 0; pp < 4; ++pp) {
                 const float ri = rsqrtf(pre0.rs[pp]);
                 const v4f a4 = gt[pp], w = pre0.w[pp];
-                buf_store_f4(rw, woff(pp), v4f{w.x - kfac[0] * ri * a4.x, w.y - kfac[1] * ri * a4.y,
-                                               w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w});
+                const v4f wn = {w.x - kfac[0] * ri * a4.x, w.y - kfac[1] * ri * a4.y,
+                                w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w};
+                buf_store_f4(rw, woff(pp), wn);
+                // sum of the new W^2 (rows past the end and columns past m contribute exact zeros:
+                // their old weights read as zero and their factors are zero)
+                total = __builtin_fmaf(wn.x, wn.x, total);
+                total = __builtin_fmaf(wn.y, wn.y, total);
+                total = __builtin_fmaf(wn.z, wn.z, total);
+                total = __builtin_fmaf(wn.w, wn.w, total);
+            }
+        } else if (MODE == kModeFull1) {
+            // V <- beta2 V + (1 - beta2) (Gt^2 + eps1) and the sum of U^2 = Gt^2 / V.  Stores out
+            // of range are dropped by the resource; their terms of the sum are masked (V reads
+            // as zero there).
+            const rsrc_t rv = vrsrc(rb);
+            const float a2 = p.alpha * p.alpha, omb = 1.f - p.beta2;
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                const bool ok = cok && (rb + er + 8 * pp < row_end);
+                const v4f a4 = gt[pp], v = pre0.v[pp];
+                const v4f g2 = {a2 * a4.x * a4.x, a2 * a4.y * a4.y, a2 * a4.z * a4.z, a2 * a4.w * a4.w};
+                const v4f vn = {p.beta2 * v.x + omb * (g2.x + p.eps1), p.beta2 * v.y + omb * (g2.y + p.eps1),
+                                p.beta2 * v.z + omb * (g2.z + p.eps1), p.beta2 * v.w + omb * (g2.w + p.eps1)};
+                buf_store_f4(rv, woff(pp), vn);
+                const float u2 = ((g2.x / vn.x + g2.y / vn.y) + (g2.z / vn.z + g2.w / vn.w));
+                total += ok ? u2 : 0.f;
+            }
+        } else if (MODE == kModeFull2) {
+            const rsrc_t rw = wrsrc(rb);
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                const bool ok = cok && (rb + er + 8 * pp < row_end);
+                const v4f a4 = gt[pp], w = pre0.w[pp], v = pre0.v[pp];
+                const v4f wn = {w.x - kfull * rsqrtf(v.x) * a4.x, w.y - kfull * rsqrtf(v.y) * a4.y,
+                                w.z - kfull * rsqrtf(v.z) * a4.z, w.w - kfull * rsqrtf(v.w) * a4.w};
+                buf_store_f4(rw, woff(pp), wn);
+                const float w2 = ((wn.x * wn.x + wn.y * wn.y) + (wn.z * wn.z + wn.w * wn.w));
+                total += ok ? w2 : 0.f;
             }
         } else if (MODE == kModeStats) {
             // squares of state A^T (alpha^2 is applied to the sums at the end): column sums
@@ -433,7 +487,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 if (li == 0 && dok[jt]) stg(M.colpart + (long long)it.rblock * m + d0[jt] + v, p.alpha * p.alpha * c);
             }
     }
-    if (MODE == kModeRms) {
+    if (kTotals) {
         float t = total;
         t += __shfl_xor(t, 32);
         t += __shfl_xor(t, 16);
@@ -470,6 +524,12 @@ hipError_t launch_mode_vec(const MatDev* mats, const WorkItem* items, int nitems
     case kModeFactored:
         hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
+    case kModeFull1:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeFull2:
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
     default:
         return hipErrorInvalidValue;
     }
@@ -496,6 +556,12 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
         break;
     case kModeFactored:
         hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeFull1:
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeFull2:
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;

@@ -113,6 +113,12 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
     case kModeFactored:
         hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
+    case kModeFull1:
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
+    case kModeFull2:
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
+        break;
     default:
         return hipErrorInvalidValue;
     }

@@ -21,8 +21,9 @@ __device__ __forceinline__ float half_wave_sum(float v)
 
 // Per-lane state that lives across the row loop of one workgroup.
 struct EpilogueLane {
-    float colsum;   // kModeStats: sum of Gt^2 down this lane's column; kModeRms: running total
-    float kfac;     // per-column factor of kModeFactored / kModeRms
+    float colsum;   // kModeStats: sum of Gt^2 down this lane's column; otherwise this lane's running total
+                    // (kModeRms / kModeFull1: of U^2; kModeFactored / kModeFull2: of the new W^2)
+    float kfac;     // per-column factor of kModeFactored / kModeRms; step factor of kModeFull2
 };
 
 template <int MODE>
@@ -34,8 +35,14 @@ __device__ __forceinline__ EpilogueLane epilogue_begin(const MatDev& M, const De
     e.kfac = 0.f;
     if (MODE == kModeFactored) {
         // U = Gt / sqrt(R_i K_j / mean R), scaled by lr and the RMS clip factor
-        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1);
-        e.kfac = jok ? p.coef * p.alpha * clip * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + j)) : 0.f;
+        // (scal[2]: the parameter scale max(eps2, RMS(W)), or 1)
+        const float meanR = ldg(M.scal), clip = ldg(M.scal + 1), ps = ldg(M.scal + 2);
+        e.kfac = jok ? p.coef * p.alpha * clip * ps * sqrtf(meanR) * rsqrtf(ldg(M.col_stat + j)) : 0.f;
+    }
+    if (MODE == kModeFull2) {
+        // U = Gt / sqrt(V_ij), scaled the same way
+        const float clip = ldg(M.scal + 1), ps = ldg(M.scal + 2);
+        e.kfac = jok ? p.coef * p.alpha * clip * ps : 0.f;
     }
     if (MODE == kModeRms) {
         const float meanR = ldg(M.scal);
@@ -48,8 +55,9 @@ __device__ __forceinline__ EpilogueLane epilogue_begin(const MatDev& M, const De
 // fetched one tile ahead so that their latency overlaps the previous tile's work.
 template <int MODE>
 struct TilePre {
-    float w[(MODE == kModeSgd || MODE == kModeFactored) ? 16 : 1];
+    float w[(MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2) ? 16 : 1];
     float rs[(MODE == kModeRms || MODE == kModeFactored) ? 16 : 1];
+    float v[(MODE == kModeFull1 || MODE == kModeFull2) ? 16 : 1];
 };
 
 // Row of register v of this lane, relative to the tile's first row.
@@ -67,12 +75,20 @@ __device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev&
     // back to back; only the stores are predicated.
     const uint32_t jc = jok ? (uint32_t)j : m32 - 1u;
     const int last = (int)(row_end - 1 - rb);          // last valid row of the tile, relative
-    if (MODE == kModeSgd || MODE == kModeFactored) {
+    if (MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2) {
         const float* tb = M.weight + rb * M.m;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
             pre.w[v] = ldg(tb + (rr * m32 + jc));
+        }
+    }
+    if (MODE == kModeFull1 || MODE == kModeFull2) {
+        const float* tb = M.vfull + rb * M.m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+            pre.v[v] = ldg(tb + (rr * m32 + jc));
         }
     }
     if (MODE == kModeRms || MODE == kModeFactored) {
@@ -132,8 +148,30 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
         float* wb = M.weight + rb * m;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            if (jok && tile_row(v, g) < rows_here)
-                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v]);
+            if (jok && tile_row(v, g) < rows_here) {
+                const float wn = pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v];
+                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), wn);
+                e.colsum = __builtin_fmaf(wn, wn, e.colsum);
+            }
+    } else if (MODE == kModeFull1) {
+        float* vb = M.vfull + rb * m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (jok && tile_row(v, g) < rows_here) {
+                const float gt = p.alpha * acc[v];
+                const float vn = p.beta2 * pre.v[v] + (1.f - p.beta2) * (gt * gt + p.eps1);
+                stg(vb + ((uint32_t)tile_row(v, g) * m32 + j32), vn);
+                e.colsum += gt * gt / vn;
+            }
+    } else if (MODE == kModeFull2) {
+        float* wb = M.weight + rb * m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (jok && tile_row(v, g) < rows_here) {
+                const float wn = pre.w[v] - e.kfac * rsqrtf(pre.v[v]) * acc[v];
+                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), wn);
+                e.colsum = __builtin_fmaf(wn, wn, e.colsum);
+            }
     }
     if (MODE == kModeStats) {
         // row sums over this wave's 32 columns, then over the 4 waves in a fixed order
@@ -165,7 +203,7 @@ __device__ __forceinline__ void epilogue_end(const MatDev& M, const WorkItem& it
         e.colsum += __shfl_xor(e.colsum, 32);
         if (g == 0 && jok) stg(M.colpart + (long long)it.rblock * M.m + j, e.colsum);
     }
-    if (MODE == kModeRms) {
+    if (MODE == kModeRms || MODE == kModeFactored || MODE == kModeFull1 || MODE == kModeFull2) {
         float s = half_wave_sum(e.colsum);
         s += __shfl_xor(s, 32);
         if (lane == 0) lds_red[wave][0] = s;

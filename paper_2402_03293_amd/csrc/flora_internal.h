@@ -12,12 +12,14 @@ struct MatDev {
     float* state;
     float* row_stat;
     float* col_stat;
+    float* vfull;       // n x m second moment of the unfactored rule
+    float* wsumsq;      // 1 float: sum of W^2, read for the parameter scale and refreshed by the update
     void* out;          // flora_decompress destination
     float* T;           // r x r transfer matrix (workspace)
     float* rowpart;     // [ncolchunks][n] partial row sums of Gt^2 (workspace)
     float* colpart;     // [nrowblocks][m] partial column sums of Gt^2 (workspace)
-    float* itempart;    // [nitems] per-workgroup partial sums of U^2 (workspace)
-    float* scal;        // [4]: mean(R), clip scale, spare, spare (workspace)
+    float* itempart;    // [nitems] per-workgroup partial sums of U^2, later of the new W^2 (workspace)
+    float* scal;        // [4]: mean(R), clip scale, parameter scale max(eps2, RMS(W)) or 1, spare (workspace)
     long long n, m;
     uint32_t seed_lo, seed_hi, seedn_lo, seedn_hi;   // used by the transfer kernels only
     int ncolchunks, nrowblocks;   // decompress tiling of this matrix
@@ -52,12 +54,16 @@ enum DecompressMode : int {
     kModeSgd = 1,      // W <- W - coef * state A^T
     kModeStats = 2,    // partial row / column sums of (alpha state A^T)^2
     kModeRms = 3,      // partial sums of U^2
-    kModeFactored = 4  // W <- W - lr * scale * Gt / sqrt(R_i K_j / mean R)
+    kModeFactored = 4, // W <- W - lr * scale * Gt / sqrt(R_i K_j / mean R); partial sums of the new W^2
+    kModeFull1 = 5,    // V <- beta2 V + (1 - beta2) (Gt^2 + eps1); partial sums of U^2 = Gt^2 / V
+    kModeFull2 = 6     // W <- W - lr * scale * Gt / sqrt(V); partial sums of the new W^2
 };
 
 struct DecompressParams {
     float alpha;   // scale of Gt
-    float coef;    // lr * alpha (SGD) or lr (factored)
+    float coef;    // lr * alpha (SGD) or lr (factored, unfactored)
+    float beta2;   // kModeFull1: decay of V
+    float eps1;    // kModeFull1: added to Gt^2
 };
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -163,7 +169,10 @@ hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int
 hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s);
 hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, hipStream_t s);
 hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);
-hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, hipStream_t s);
+hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
+                               hipStream_t s);
+hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s);
+hipError_t launch_weight_sumsq(const MatDev* mats, int count, float* partials, hipStream_t s);
 hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s);
 
 // Tiling constants the host needs to build work tables.
@@ -173,5 +182,6 @@ constexpr int kDecompressCols = 128;     // columns per workgroup, 4-byte-per-la
 constexpr int kDecompressColsVec = 256;  // columns per workgroup, 16-byte-per-lane bf16 decompress kernel
 constexpr int kDecompressRows = 256;     // rows per workgroup, both decompress kernels
 constexpr int kApplyTRows = 32;          // rows per workgroup, state <- state T
+constexpr int kSumsqBlocks = 256;        // workgroups per matrix, sum of W^2
 
 }  // namespace flora

@@ -1,5 +1,5 @@
-// Small grouped kernels around the factored second-moment rule (the Adafactor
-// rule the paper uses as base optimizer, Section 3.1) and the end of an
+// Small grouped kernels around the Adafactor rules (the base optimizer of the
+// paper's experiments, Section 3.1; unfactored variant, Section 3.3) and the end of an
 // accumulation cycle (Algorithm 1: the accumulator starts each cycle at zero).
 // All reductions run in a fixed order, so results are reproducible bit for bit.
 #include "flora_internal.h"
@@ -53,19 +53,82 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const MatDev* __res
 }
 
 // scal[1] <- 1 / max(1, RMS(U) / clip_d), RMS(U)^2 = sum of the workgroup partials / (n m)
-__global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restrict__ mats, float clip_d)
+// (1 when clip_d == 0: no clipping);  scal[2] <- max(eps2, RMS(W)) from the caller's sum of W^2
+// when the step is relative to the parameter scale, else 1.
+__global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restrict__ mats, float clip_d,
+                                                           int scale_parameter, float eps2)
 {
     __shared__ float lds[256];
     const MatDev& M = mats[blockIdx.x];
     const int tid = threadIdx.x;
+    float tot = 0.f;
+    if (clip_d > 0.f) {
+        float s = 0.f;
+        for (int i = tid; i < M.nitems; i += 256) s += M.itempart[i];
+        tot = block_sum_256(s, lds);
+    }
+    if (tid == 0) {
+        float clip = 1.f;
+        if (clip_d > 0.f) {
+            const float rms = sqrtf(tot / ((float)M.n * (float)M.m));
+            const float d = rms / clip_d;
+            clip = 1.f / (d > 1.f ? d : 1.f);
+        }
+        M.scal[1] = clip;
+        float ps = 1.f;
+        if (scale_parameter) {
+            const float rmsw = sqrtf(M.wsumsq[0] / ((float)M.n * (float)M.m));
+            ps = rmsw > eps2 ? rmsw : eps2;
+        }
+        M.scal[2] = ps;
+    }
+}
+
+// wsumsq <- sum of the update pass's per-workgroup partial sums of the new W^2
+__global__ __launch_bounds__(256) void wsumsq_finalize_kernel(const MatDev* __restrict__ mats)
+{
+    __shared__ float lds[256];
+    const MatDev& M = mats[blockIdx.x];
+    if (!M.wsumsq) return;
+    const int tid = threadIdx.x;
     float s = 0.f;
     for (int i = tid; i < M.nitems; i += 256) s += M.itempart[i];
     const float tot = block_sum_256(s, lds);
-    if (tid == 0) {
-        const float rms = sqrtf(tot / ((float)M.n * (float)M.m));
-        const float d = rms / clip_d;
-        M.scal[1] = 1.f / (d > 1.f ? d : 1.f);
+    if (tid == 0) M.wsumsq[0] = tot;
+}
+
+// Sum of W^2 from scratch: workgroup b of matrix l sums the float4s b, b + 256, ... of W
+// (and the last n m % 4 values in workgroup 0) into partials[l][b].
+__global__ __launch_bounds__(256) void weight_sumsq_kernel(const MatDev* __restrict__ mats,
+                                                           float* __restrict__ partials)
+{
+    __shared__ float lds[256];
+    const MatDev& M = mats[blockIdx.y];
+    const long long total = M.n * M.m, total4 = total >> 2;
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    for (long long i = (long long)blockIdx.x * 256 + tid; i < total4; i += (long long)kSumsqBlocks * 256) {
+        const v4f w = ldg4(M.weight + 4 * i);
+        s = __builtin_fmaf(w.x, w.x, s);
+        s = __builtin_fmaf(w.y, w.y, s);
+        s = __builtin_fmaf(w.z, w.z, s);
+        s = __builtin_fmaf(w.w, w.w, s);
     }
+    if (blockIdx.x == 0 && tid < (int)(total & 3)) {
+        const float w = ldg(M.weight + 4 * total4 + tid);
+        s = __builtin_fmaf(w, w, s);
+    }
+    const float tot = block_sum_256(s, lds);
+    if (tid == 0) partials[(long long)blockIdx.y * kSumsqBlocks + blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void weight_sumsq_finalize_kernel(const MatDev* __restrict__ mats,
+                                                                    const float* __restrict__ partials)
+{
+    __shared__ float lds[256];
+    const MatDev& M = mats[blockIdx.x];
+    const float tot = block_sum_256(partials[(long long)blockIdx.x * kSumsqBlocks + threadIdx.x], lds);
+    if (threadIdx.x == 0) M.wsumsq[0] = tot;
 }
 
 __global__ __launch_bounds__(256) void zero_state_kernel(const MatDev* __restrict__ mats, int r)
@@ -86,10 +149,28 @@ hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, flo
     return hipGetLastError();
 }
 
-hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, hipStream_t s)
+hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
+                               hipStream_t s)
 {
     if (count == 0) return hipSuccess;
-    hipLaunchKernelGGL(rms_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, clip_d);
+    hipLaunchKernelGGL(rms_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, clip_d,
+                       scale_parameter, eps2);
+    return hipGetLastError();
+}
+
+hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(wsumsq_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_sumsq(const MatDev* mats, int count, float* partials, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    static_assert(kSumsqBlocks == 256, "one partial per thread of the finalize kernel");
+    hipLaunchKernelGGL(weight_sumsq_kernel, dim3(kSumsqBlocks, (unsigned)count), dim3(256), 0, s, mats, partials);
+    hipLaunchKernelGGL(weight_sumsq_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, partials);
     return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@ ERR_UNSUPPORTED = -2
 ERR_DEVICE = -3
 RULE_SGD = 0
 RULE_FACTORED = 1
+RULE_UNFACTORED = 2
 
 _LIB_PATH = Path(__file__).resolve().parent / "libflora.so"
 
@@ -35,6 +36,8 @@ class Matrix(ctypes.Structure):
         ("m", ctypes.c_int64),
         ("seed", ctypes.c_uint64),
         ("seed_next", ctypes.c_uint64),
+        ("second_moment", ctypes.c_void_p),
+        ("weight_sumsq", ctypes.c_void_p),
     ]
 
 
@@ -48,6 +51,8 @@ class Update(ctypes.Structure):
         ("eps1", ctypes.c_float),
         ("clip_d", ctypes.c_float),
         ("zero_state_after", ctypes.c_int),
+        ("scale_parameter", ctypes.c_int),
+        ("eps2", ctypes.c_float),
     ]
 
 
@@ -85,6 +90,10 @@ def lib():
         L.flora_apply_update.restype = ci
         L.flora_fused_step.argtypes = [MP, ci, ci, ci, ci, cf, cf, ci, ctypes.POINTER(Update), vp]
         L.flora_fused_step.restype = ci
+        L.flora_weight_sumsq.argtypes = [MP, ci, vp]
+        L.flora_weight_sumsq.restype = ci
+        L.flora_adafactor_schedule.argtypes = [ctypes.c_uint64, ctypes.POINTER(cf), ctypes.POINTER(cf)]
+        L.flora_adafactor_schedule.restype = None
         L.flora_debug_generate.argtypes = [ctypes.c_uint64, ctypes.c_int64, ci, vp, vp, vp]
         L.flora_debug_generate.restype = ci
         L.flora_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -111,7 +120,8 @@ def lib():
 
 EXPORTS = [
     "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_apply_update",
-    "flora_fused_step", "flora_debug_generate", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
+    "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
+    "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
     "flora_workspace_bytes", "flora_set_tuning",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
@@ -126,7 +136,7 @@ def _ptr(t) -> Optional[int]:
 
 
 def matrices(n_m: Sequence, grads=None, weights=None, states=None, row_stats=None, col_stats=None,
-             seeds=None, seeds_next=None):
+             seeds=None, seeds_next=None, second_moments=None, weight_sumsqs=None):
     """Builds a ctypes array of flora_matrix_t.  Each argument is a sequence of
     torch tensors (or raw device addresses) or None."""
     count = len(n_m)
@@ -138,6 +148,8 @@ def matrices(n_m: Sequence, grads=None, weights=None, states=None, row_stats=Non
         arr[l].state = _ptr(states[l]) if states is not None else None
         arr[l].row_stat = _ptr(row_stats[l]) if row_stats is not None else None
         arr[l].col_stat = _ptr(col_stats[l]) if col_stats is not None else None
+        arr[l].second_moment = _ptr(second_moments[l]) if second_moments is not None else None
+        arr[l].weight_sumsq = _ptr(weight_sumsqs[l]) if weight_sumsqs is not None else None
         arr[l].seed = int(seeds[l]) if seeds is not None else 0
         arr[l].seed_next = int(seeds_next[l]) if seeds_next is not None else 0
     return arr
@@ -208,7 +220,8 @@ def fields(mats):
     import numpy as np
     dt = np.dtype([("grad", np.uint64), ("weight", np.uint64), ("state", np.uint64),
                    ("row_stat", np.uint64), ("col_stat", np.uint64), ("n", np.int64), ("m", np.int64),
-                   ("seed", np.uint64), ("seed_next", np.uint64)])
+                   ("seed", np.uint64), ("seed_next", np.uint64),
+                   ("second_moment", np.uint64), ("weight_sumsq", np.uint64)])
     return np.frombuffer(mats, dtype=dt)
 
 
@@ -217,12 +230,32 @@ def workspace_bytes(mats, r: int) -> int:
 
 
 def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False) -> Update:
-    return Update(RULE_SGD, lr, alpha, 0.0, 0.0, 0.0, int(zero_state_after))
+    return Update(RULE_SGD, lr, alpha, 0.0, 0.0, 0.0, int(zero_state_after), 0, 0.0)
 
 
 def factored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
-                    zero_state_after: bool = False) -> Update:
-    return Update(RULE_FACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after))
+                    zero_state_after: bool = False, scale_parameter: bool = False,
+                    eps2: float = 1e-3) -> Update:
+    return Update(RULE_FACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after),
+                  int(scale_parameter), eps2)
+
+
+def unfactored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
+                      zero_state_after: bool = False, scale_parameter: bool = False,
+                      eps2: float = 1e-3) -> Update:
+    return Update(RULE_UNFACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after),
+                  int(scale_parameter), eps2)
+
+
+def weight_sumsq(mats, stream=None):
+    _check(lib().flora_weight_sumsq(mats, len(mats), _stream(stream)), "flora_weight_sumsq")
+
+
+def adafactor_schedule(t: int):
+    """(rho_t, beta2_t) of the published schedules for step t = 1, 2, ..."""
+    rho, beta2 = ctypes.c_float(0.0), ctypes.c_float(0.0)
+    lib().flora_adafactor_schedule(int(t), ctypes.byref(rho), ctypes.byref(beta2))
+    return rho.value, beta2.value
 
 
 def set_tuning(name: str, value: int):

@@ -28,8 +28,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(flora.Matrix) == 5 * 8 + 2 * 8 + 2 * 8
-    assert ctypes.sizeof(flora.Update) == 7 * 4
+    assert ctypes.sizeof(flora.Matrix) == 5 * 8 + 2 * 8 + 2 * 8 + 2 * 8
+    assert ctypes.sizeof(flora.Update) == 9 * 4
+    assert flora.Matrix.second_moment.offset == 72 and flora.Matrix.weight_sumsq.offset == 80
+    assert flora.Update.scale_parameter.offset == 28 and flora.Update.eps2.offset == 32
 
 
 def test_status_strings_and_version():
@@ -89,7 +91,7 @@ def test_update_validation():
     assert L.flora_apply_update(ok, 1, 16, flora.F32, None, None) == flora.ERR_INVALID
     assert L.flora_apply_update(ok, 1, 16, flora.BF16, ctypes.byref(sgd), None) == flora.ERR_UNSUPPORTED
     assert L.flora_apply_update(ok, 1, 16, 5, ctypes.byref(sgd), None) == flora.ERR_INVALID
-    bad_rule = flora.Update(9, 0.1, 1.0, 0, 0, 0, 0)
+    bad_rule = flora.Update(9, 0.1, 1.0, 0, 0, 0, 0, 0, 0)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(bad_rule), None) == flora.ERR_INVALID
     fac = flora.factored_update(0.1, 1.0, 0.0, 1e-30, 1.0)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(fac), None) == flora.ERR_INVALID  # no R, K
@@ -129,3 +131,29 @@ def test_workload_tallies_match_the_configurations():
         wl = workloads.workload(i)
         assert (len(wl.shapes), wl.elements) == (cnt, el)
     assert workloads.workload(4).state_elements * 4 == 1384120320
+
+
+def test_adafactor_rules_validation_and_schedule_helper():
+    import ctypes as C
+    L = flora.lib()
+    base = dict(grads=[0x1000], weights=[0x2000], states=[0x3000], seeds=[1])
+    no_v = flora.matrices([(16, 16)], **base)
+    with_v = flora.matrices([(16, 16)], second_moments=[0x5000], **base)
+    unf = flora.unfactored_update(0.1, 1.0, 0.0, 1e-30, 1.0)
+    assert L.flora_apply_update(no_v, 1, 16, flora.F32, C.byref(unf), None) == flora.ERR_INVALID
+    scaled = flora.unfactored_update(0.1, 1.0, 0.0, 1e-30, 1.0, scale_parameter=True)
+    assert L.flora_apply_update(with_v, 1, 16, flora.F32, C.byref(scaled), None) == flora.ERR_INVALID
+    bad_b = flora.unfactored_update(0.1, 1.0, -0.1, 1e-30, 1.0)
+    assert L.flora_apply_update(with_v, 1, 16, flora.F32, C.byref(bad_b), None) == flora.ERR_INVALID
+    alias = flora.matrices([(16, 16)], second_moments=[0x2000], **base)
+    assert L.flora_apply_update(alias, 1, 16, flora.F32, C.byref(unf), None) == flora.ERR_INVALID
+    odd = flora.matrices([(16, 16)], second_moments=[0x5004], **base)
+    assert L.flora_apply_update(odd, 1, 16, flora.F32, C.byref(unf), None) == flora.ERR_INVALID
+    assert L.flora_weight_sumsq(no_v, 1, None) == flora.ERR_INVALID
+    assert L.flora_weight_sumsq(None, 1, None) == flora.ERR_INVALID
+    assert L.flora_weight_sumsq(no_v, 0, None) == flora.OK
+    # published schedules: rho_t = min(1e-2, 1/sqrt(t)), beta2_t = 1 - t^-0.8
+    assert flora.adafactor_schedule(1) == (pytest.approx(1e-2, rel=1e-6), 0.0)
+    assert flora.adafactor_schedule(32)[1] == pytest.approx(0.9375, rel=1e-6)
+    assert flora.adafactor_schedule(40000)[0] == pytest.approx(5e-3, rel=1e-6)
+    L.flora_adafactor_schedule(5, None, None)          # NULL outputs are allowed
