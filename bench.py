@@ -44,6 +44,10 @@ def parse_args():
                     help="bracket the launches of every N-th timed step with HIP events")
     ap.add_argument("--tune", default="", help="launch-shape overrides for sweeps: name=value[,name=value...] "
                                                "(names of flora_set_tuning)")
+    ap.add_argument("--rule", default=None, choices=["adafactor", "unfactored"],
+                    help="replace the workload's update rule by the whole Adafactor step (factored second "
+                         "moment, published schedules, step relative to the carried parameter scale) or by "
+                         "its unfactored variant")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     return ap.parse_args()
@@ -92,8 +96,15 @@ def main():
     grad_sets = [workloads.make_grad_set(wl, gen, dev) for _ in range(nsets)]
     W = workloads.make_weight_set(wl, gen, dev)
     states = [torch.zeros((n, r), device=dev, dtype=torch.float32) for n, _ in shapes]
-    row_stats = col_stats = None
-    if wl.rule == "factored":
+    row_stats = col_stats = second = sumsq = None
+    rule = args.rule or wl.rule
+    if rule in ("adafactor", "unfactored"):
+        sumsq_buf = torch.zeros((count, 4), device=dev)
+        sumsq = [sumsq_buf[i] for i in range(count)]
+    if rule == "unfactored":
+        # resumed from a typical second moment (from zero the first steps are sign descent)
+        second = [torch.full((n, m), 1.0, device=dev) for n, m in shapes]
+    if rule in ("factored", "adafactor"):
         row_stats = [torch.zeros((n,), device=dev) for n, _ in shapes]
         col_stats = [torch.zeros((m,), device=dev) for _, m in shapes]
     torch.cuda.synchronize()
@@ -105,7 +116,8 @@ def main():
 
     # one descriptor array per gradient set, built once; only the seed fields change later
     mats_sets = [flora.matrices(shapes, grads=grad_sets[g], weights=W, states=states, row_stats=row_stats,
-                                col_stats=col_stats, seeds=seeds, seeds_next=seeds) for g in range(nsets)]
+                                col_stats=col_stats, seeds=seeds, seeds_next=seeds, second_moments=second,
+                                weight_sumsqs=sumsq) for g in range(nsets)]
     views = [flora.fields(mt) for mt in mats_sets]
 
     def set_seeds(cur, nxt=None):
@@ -113,7 +125,19 @@ def main():
             v["seed"][:] = cur
             v["seed_next"][:] = cur if nxt is None else nxt
 
-    if wl.rule == "factored":
+    alpha_u = 1.0 / wl.tau if wl.algorithm == 1 else 1.0
+    zero_after = wl.algorithm == 1
+
+    def adafactor_update(t):
+        # step t = 1, 2, ... of the published schedules, relative to the parameter scale
+        rho, beta2 = flora.adafactor_schedule(t)
+        mk = flora.factored_update if rule == "adafactor" else flora.unfactored_update
+        return mk(rho, alpha_u, beta2, 1e-30, 1.0, zero_state_after=zero_after, scale_parameter=True, eps2=1e-3)
+
+    if rule in ("adafactor", "unfactored"):
+        flora.weight_sumsq(mats_sets[0], stream)     # once: the updates carry it from here on
+        upd = adafactor_update(1)
+    elif wl.rule == "factored":
         ex = wl.extra
         upd = flora.factored_update(wl.lr, 1.0 / wl.tau, ex["beta2"], ex["eps1"], ex["clip_d"],
                                     zero_state_after=True)
@@ -136,10 +160,13 @@ def main():
         else:
             fn()
 
-    tstate = {"t": 0, "gi": 0}
+    tstate = {"t": 0, "gi": 0, "u": 0}
 
     def one_step():
-        nonlocal seeds, epoch
+        nonlocal seeds, epoch, upd
+        if rule in ("adafactor", "unfactored"):
+            tstate["u"] += 1
+            upd = adafactor_update(tstate["u"])
         if wl.algorithm == 1:
             for _ in range(wl.tau):
                 mt = mats_sets[tstate["gi"] % nsets]
@@ -194,10 +221,12 @@ def main():
     E, S = wl.elements, wl.state_elements
     alg_bytes = {
         "compress": gbytes * E + 8 * S,
-        "update": 4 * S + 8 * E if wl.rule == "sgd" else (3 * 4 * S + 8 * E),
+        "update": {"sgd": 4 * S + 8 * E, "factored": 3 * 4 * S + 8 * E, "adafactor": 3 * 4 * S + 8 * E,
+                   "unfactored": 2 * 4 * S + 20 * E}[rule],
         "transfer": 8 * S,
     }
-    alg_flops = {"compress": 2.0 * E * r, "update": 2.0 * E * r * (1 if wl.rule == "sgd" else 3),
+    alg_flops = {"compress": 2.0 * E * r,
+                 "update": 2.0 * E * r * {"sgd": 1, "factored": 3, "adafactor": 3, "unfactored": 2}[rule],
                  "transfer": sum(2.0 * m * r * r + 2.0 * n * r * r for n, m in shapes)}
     kern = {}
     for k, pairs in ev_pairs.items():
@@ -216,7 +245,7 @@ def main():
     try:
         for line in open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")):
             f = line.split()
-            if len(f) == 4 and f[0] == wl.name and f[1] == dominant:
+            if len(f) == 4 and f[0] == wl.name and f[1] == dominant and rule == wl.rule:
                 traffic = int(f[2]) + int(f[3])     # profiler-measured bytes per launch (read + written)
     except OSError:
         pass
@@ -239,19 +268,19 @@ def main():
                    "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
                    "beta": wl.beta if wl.algorithm == 2 else None,
                    "kappa": wl.kappa if wl.algorithm == 2 else None,
-                   "rule": wl.rule, "grad_sets_in_ring": nsets,
+                   "rule": rule, "grad_sets_in_ring": nsets,
                    "grad_bytes_per_step": grad_bytes_step},
         "roofline": roofline,
         "kernels": kern,
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, grad_sets, W, args.cpu_budget_gflop)
+        out["cpu_baseline"] = cpu_baseline(wl, grad_sets, W, args.cpu_budget_gflop, rule=rule)
 
     print(json.dumps(out))
 
 
-def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
+def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0, rule=None):
     """The fp64 oracle, as it stands, timed on this host over a bounded sample of the same
     workload: whole matrices taken in order until the flop budget is used (at least one)."""
     import numpy as np
@@ -260,9 +289,8 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
     import oracle
 
     r = wl.r
+    rule = rule or wl.rule
     passes = (wl.tau + 1) if wl.algorithm == 1 else 2
-    if wl.rule == "factored":
-        passes = wl.tau + 1
     chosen, fl = [], 0.0
     for l, (n, m) in enumerate(wl.shapes):
         f = 2.0 * n * m * r * passes / 1e9
@@ -275,6 +303,17 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
 
     def to64(t):
         return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+    def base_update(Wl, Gt, n, m):
+        if rule == "sgd":
+            oracle.sgd(Wl, Gt, wl.lr)
+        elif rule == "factored":
+            ex = wl.extra
+            oracle.factored_update(Wl, Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"], ex["clip_d"], wl.lr)
+        elif rule == "adafactor":
+            oracle.adafactor_step(Wl, Gt, R=np.zeros(n), K=np.zeros(m), beta2=0.0, step=1e-2)
+        else:
+            oracle.adafactor_step(Wl, Gt, V=np.ones((n, m)), beta2=0.5, step=1e-2)
 
     spent = 0.0
     nbytes = 0
@@ -298,12 +337,7 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
                     nbytes += n * m * gb
                 t0 = time.perf_counter()
                 Gt = oracle.decompress(C, m, seed, alpha=1.0 / wl.tau)
-                if wl.rule == "sgd":
-                    oracle.sgd(Wl, Gt, wl.lr)
-                else:
-                    ex = wl.extra
-                    oracle.factored_update(Wl, Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"],
-                                           ex["clip_d"], wl.lr)
+                base_update(Wl, Gt, n, m)
                 spent += time.perf_counter() - t0
             else:
                 G = to64(grad_sets[0][l])
@@ -311,7 +345,7 @@ def cpu_baseline(wl, grad_sets, W, budget_gflop, min_seconds=10.0):
                 t0 = time.perf_counter()
                 M = oracle.compress(G, r, seed, state=M, a=wl.beta, b=1.0 - wl.beta)
                 Gt = oracle.decompress(M, m, seed)
-                oracle.sgd(Wl, Gt, wl.lr)
+                base_update(Wl, Gt, n, m)
                 spent += time.perf_counter() - t0
                 nbytes += n * m * gb
     try:
