@@ -208,3 +208,80 @@ def test_workload4_accumulate_and_factored_update():
         n, m = wl.shapes[l]
         a, b = float(R[l].double().sum()) * m, float(K[l].double().sum()) * n
         assert abs(a - b) <= 1e-4 * abs(a)
+
+
+@pytest.mark.parametrize("rule", ["adafactor", "unfactored"])
+def test_workload4_shapes_whole_adafactor_step(rule):
+    """T5-3B set, r = 256, all 384 matrices per launch, the whole Adafactor step (relative step,
+    decay and parameter scale of the published schedules at step 7) with the factored or the
+    unfactored second moment, from a seeded state and second moment.  Whole matrices of the two
+    smaller shapes against the oracle; on the larger shapes the unfactored second moment (row by
+    row independent) on sampled rows, and the carried sum of squares everywhere."""
+    wl = workloads.workload(4)
+    r, count = wl.r, len(wl.shapes)
+    rng = np.random.default_rng(44)
+    gen = workloads.make_generator(wl.seed + 7, DEV)
+    W = workloads.make_weight_set(wl, gen, DEV)
+    S = [torch.randn((n, r), device=DEV, generator=gen) for n, _ in wl.shapes]
+    seeds = flora.derive_seeds(414, 0, count, 3)
+    firsts = first_of_each_shape(wl.shapes)
+    whole = [l for l in firsts if wl.shapes[l][0] * wl.shapes[l][1] <= 1024 * 4096]
+    large = [l for l in firsts if l not in whole] + [383]
+    ss = torch.zeros((count, 4), device=DEV)
+    sumsqs = [ss[l] for l in range(count)]
+    kw = dict(weights=W, states=S, seeds=seeds, weight_sumsqs=sumsqs)
+    R0 = K0 = V0 = None
+    if rule == "adafactor":
+        R = [torch.rand((n,), device=DEV, generator=gen) + 0.5 for n, _ in wl.shapes]
+        K = [torch.rand((m,), device=DEV, generator=gen) + 0.5 for _, m in wl.shapes]
+        R0 = {l: to64(R[l]) for l in whole}
+        K0 = {l: to64(K[l]) for l in whole}
+        kw.update(row_stats=R, col_stats=K)
+    else:
+        V = [torch.rand((n, m), device=DEV, generator=gen) + 0.5 for n, m in wl.shapes]
+        rows = {l: sample_rows(wl.shapes[l][0], rng) for l in large}
+        V0 = {l: to64(V[l]) for l in whole}
+        V0.update({l: to64(V[l][torch.as_tensor(rows[l], device=DEV)]) for l in large})
+        kw.update(second_moments=V)
+    W0 = {l: to64(W[l]) for l in whole}
+    S64 = {l: to64(S[l]) for l in whole}
+    if rule == "unfactored":
+        S64.update({l: to64(S[l][torch.as_tensor(rows[l], device=DEV)]) for l in large})
+    mats = flora.matrices(wl.shapes, **kw)
+    flora.weight_sumsq(mats)
+    torch.cuda.synchronize()
+    for l in (0, 100, 383):
+        assert float(ss[l, 0]) == pytest.approx(float((W[l].double() ** 2).sum()), rel=5e-6)
+    t, alpha, eps1, eps2, clip_d = 7, 1.0 / 16, 1e-30, 1e-3, 1.0
+    rho, beta2 = flora.adafactor_schedule(t)
+    mk = flora.factored_update if rule == "adafactor" else flora.unfactored_update
+    flora.apply_update(mats, r, flora.F32, mk(rho, alpha, beta2, eps1, clip_d, scale_parameter=True, eps2=eps2))
+    torch.cuda.synchronize()
+    orho, obeta2 = oracle.adafactor_schedule(t)
+    worst = 0.0
+    for l in whole:
+        n, m = wl.shapes[l]
+        Gt = oracle.decompress(S64[l], m, int(seeds[l]), alpha=alpha)
+        if rule == "adafactor":
+            Wr, Rr, Kr = oracle.adafactor_step(W0[l], Gt, R=R0[l], K=K0[l], beta2=obeta2, eps1=eps1, eps2=eps2,
+                                               clip_d=clip_d, step=orho)
+            assert rel_fro(to64(R[l]), Rr) < TOL_BF16 and rel_fro(to64(K[l]), Kr) < TOL_BF16
+        else:
+            Wr, Vr = oracle.adafactor_step(W0[l], Gt, V=V0[l], beta2=obeta2, eps1=eps1, eps2=eps2, clip_d=clip_d,
+                                           step=orho)
+            assert rel_fro(to64(V[l]), Vr) < TOL_BF16
+        worst = max(worst, rel_fro(to64(W[l]) - W0[l], Wr - W0[l]))
+        assert float(ss[l, 0]) == pytest.approx(float((Wr ** 2).sum()), rel=1e-4)
+    print("workload 4 shapes, %s: worst update err %.2e" % (rule, worst))
+    assert worst < TOL_BF16
+    if rule == "unfactored":
+        for l in large:
+            n, m = wl.shapes[l]
+            Gt = oracle.decompress(S64[l], m, int(seeds[l]), alpha=alpha)
+            Vr = obeta2 * V0[l] + (1.0 - obeta2) * (Gt * Gt + eps1)     # the elementwise EMA, rows independent
+            got = to64(V[l][torch.as_tensor(rows[l], device=DEV)])
+            assert rel_fro(got, Vr) < TOL_BF16
+            assert (np.linalg.norm(got - Vr, axis=1) / np.linalg.norm(Vr, axis=1)).max() < TOL_BF16
+    for l in range(0, count, 37):
+        assert float(ss[l, 0]) == pytest.approx(float((W[l].double() ** 2).sum()), rel=5e-6)
+        assert bool(torch.isfinite(W[l]).all())
