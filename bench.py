@@ -48,6 +48,11 @@ def parse_args():
                     help="replace the workload's update rule by the whole Adafactor step (factored second "
                          "moment, published schedules, step relative to the carried parameter scale) or by "
                          "its unfactored variant")
+    ap.add_argument("--momentum", default=None, choices=["folded", "direct"],
+                    help="Algorithm-1 workloads only: feed the accumulation cycle into a compressed momentum "
+                         "(beta 0.9) and update from that.  folded: accumulate into C under one projection, "
+                         "then M <- beta M + ((1-beta)/tau) C A_c^T A_m (flora_transfer_accumulate); direct: one "
+                         "projection for both, every micro-batch is compressed straight into M")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     return ap.parse_args()
@@ -109,6 +114,15 @@ def main():
         col_stats = [torch.zeros((m,), device=dev) for _, m in shapes]
     torch.cuda.synchronize()
 
+    if args.momentum and wl.algorithm != 1:
+        sys.stderr.write("bench.py: --momentum applies to the accumulation workloads (1, 2, 4)\n")
+        sys.exit(2)
+    mom = mom_seeds = None
+    if args.momentum:
+        mom = [torch.zeros((n, r), device=dev, dtype=torch.float32) for n, _ in shapes]
+        mom_seeds = flora.derive_seeds(4321, 0, count, 0)     # the momentum keeps its projection
+    torch.cuda.synchronize()
+
     stream = torch.cuda.current_stream()
     gseed = 1234
     epoch = 0
@@ -119,6 +133,13 @@ def main():
                                 col_stats=col_stats, seeds=seeds, seeds_next=seeds, second_moments=second,
                                 weight_sumsqs=sumsq) for g in range(nsets)]
     views = [flora.fields(mt) for mt in mats_sets]
+    mats_mom = None
+    if args.momentum:
+        # descriptors whose state is the momentum: the update reads it; in direct mode the
+        # micro-batches are compressed into it as well
+        mats_mom = [flora.matrices(shapes, grads=grad_sets[g], weights=W, states=mom, row_stats=row_stats,
+                                   col_stats=col_stats, seeds=mom_seeds, seeds_next=mom_seeds,
+                                   second_moments=second, weight_sumsqs=sumsq) for g in range(nsets)]
 
     def set_seeds(cur, nxt=None):
         for v in views:
@@ -127,6 +148,9 @@ def main():
 
     alpha_u = 1.0 / wl.tau if wl.algorithm == 1 else 1.0
     zero_after = wl.algorithm == 1
+
+    if args.momentum:
+        alpha_u, zero_after = 1.0, False     # the momentum is not reset and its decompression carries no 1/tau
 
     def adafactor_update(t):
         # step t = 1, 2, ... of the published schedules, relative to the parameter scale
@@ -145,6 +169,16 @@ def main():
         upd = flora.sgd_update(wl.lr, 1.0 / wl.tau, zero_state_after=True)
     else:
         upd = flora.sgd_update(wl.lr, 1.0)
+
+    upd_mom = None
+    if args.momentum:
+        if rule in ("adafactor", "unfactored"):
+            upd_mom = upd
+        elif wl.rule == "factored":
+            ex = wl.extra
+            upd_mom = flora.factored_update(wl.lr, 1.0, ex["beta2"], ex["eps1"], ex["clip_d"])
+        else:
+            upd_mom = flora.sgd_update(wl.lr, 1.0)
 
     ev_pairs = {"compress": [], "update": [], "transfer": []}
     record = {"on": False}
@@ -167,7 +201,32 @@ def main():
         if rule in ("adafactor", "unfactored"):
             tstate["u"] += 1
             upd = adafactor_update(tstate["u"])
-        if wl.algorithm == 1:
+        if wl.algorithm == 1 and args.momentum:
+            beta = 0.9
+            for i in range(wl.tau):
+                g = tstate["gi"] % nsets
+                tstate["gi"] += 1
+                if args.momentum == "direct":
+                    mt = mats_mom[g]
+                    a_, b_ = (beta if i == 0 else 1.0), (1.0 - beta) / wl.tau
+                    timed("compress", lambda: flora.compress(mt, r, gdt, a_, b_, stream))
+                else:
+                    mt = mats_sets[g]
+                    timed("compress", lambda: flora.compress(mt, r, gdt, 1.0, 1.0, stream))
+            if args.momentum == "folded":
+                for v in views:
+                    v["seed_next"][:] = mom_seeds
+                mt = mats_sets[0]
+                timed("transfer", lambda: flora.transfer_accumulate(mt, r, beta, (1.0 - beta) / wl.tau, mom, stream))
+                for st_ in states:
+                    st_.zero_()
+            mt = mats_mom[0]
+            u_ = upd if rule in ("adafactor", "unfactored") else upd_mom
+            timed("update", lambda: flora.apply_update(mt, r, flora.F32, u_, stream))
+            epoch += 1
+            seeds = flora.derive_seeds(gseed, 0, count, epoch)
+            set_seeds(seeds)
+        elif wl.algorithm == 1:
             for _ in range(wl.tau):
                 mt = mats_sets[tstate["gi"] % nsets]
                 tstate["gi"] += 1
@@ -223,7 +282,7 @@ def main():
         "compress": gbytes * E + 8 * S,
         "update": {"sgd": 4 * S + 8 * E, "factored": 3 * 4 * S + 8 * E, "adafactor": 3 * 4 * S + 8 * E,
                    "unfactored": 2 * 4 * S + 20 * E}[rule],
-        "transfer": 8 * S,
+        "transfer": 8 * S if not args.momentum else 12 * S,     # folded: reads C, reads and writes M
     }
     alg_flops = {"compress": 2.0 * E * r,
                  "update": 2.0 * E * r * {"sgd": 1, "factored": 3, "adafactor": 3, "unfactored": 2}[rule],
@@ -268,7 +327,7 @@ def main():
                    "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
                    "beta": wl.beta if wl.algorithm == 2 else None,
                    "kappa": wl.kappa if wl.algorithm == 2 else None,
-                   "rule": rule, "grad_sets_in_ring": nsets,
+                   "rule": rule, "momentum_from_accumulator": args.momentum, "grad_sets_in_ring": nsets,
                    "grad_bytes_per_step": grad_bytes_step},
         "roofline": roofline,
         "kernels": kern,

@@ -122,6 +122,17 @@ int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha,
  * seed by seed_next afterwards. */
 int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream);
 
+/* A compressed accumulator folded into a compressed moving average kept under another
+ * projection (Algorithm 1's decompressed mean fed to Algorithm 2's EMA line: a = beta,
+ * b = (1 - beta) / tau; the paper notes that the transfer extends to other EMA statistics,
+ * Section 2.4), with no n x m pass:
+ *     dst[l] <- a * dst[l] + b * state A(seed)^T A(seed_next)
+ * equal to compressing the decompressed state, computed as T = A(seed)^T A(seed_next) and
+ * state T entirely in fp32.  `dst` is a HOST array of `count` DEVICE pointers to n x r fp32
+ * buffers, none of which may be the matrix's own state.  Uses state, n, m, seed, seed_next. */
+int flora_transfer_accumulate(const flora_matrix_t* mats, int count, int r, float a, float b,
+                              float* const* dst, void* hip_stream);
+
 /* Decompression fused with the base optimizer's update; Gt is never stored:
  *   FLORA_RULE_SGD:       W <- W - lr * Gt            (Section 2.2, update rule)
  *   FLORA_RULE_FACTORED:  Adafactor, the base optimizer of the paper's experiments

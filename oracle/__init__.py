@@ -189,6 +189,16 @@ def transfer(M, m: int, seed_old: int, seed_new: int, return_T: bool = False):
     return (out, T) if return_T else out
 
 
+def transfer_accumulate(dst, src, m: int, seed_src: int, seed_dst: int, a: float, b: float) -> np.ndarray:
+    """dst <- a dst + b (src A_src^T) A_dst, taken literally: the n x m decompression of
+    ``src`` (Algorithm 1, decompression line) is compressed again under the destination's
+    projection with the EMA coefficients (Algorithm 2, EMA line)."""
+    src = _f64c(src)
+    r = src.shape[1]
+    Gt = decompress(src, m, seed_src, alpha=1.0)
+    return compress(Gt, r, seed_dst, state=dst, a=a, b=b)
+
+
 def sgd(W, Gt, lr: float) -> np.ndarray:
     W = _f64c(W).copy()
     Gt = _f64c(Gt)

@@ -613,22 +613,25 @@ static int decompress_chunk(const flora_matrix_t* mats, int count, int r, float 
     return run_decompress(p, sa, r, kModeOut, out_dtype == FLORA_BF16, dp, s);
 }
 
-static int transfer_chunk(const flora_matrix_t* mats, int count, int r, hipStream_t s)
+// dst == nullptr: state <- state T in place; else dst[l] <- ca * dst[l] + cb * (state T)
+static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* const* dst, float ca, float cb,
+                          hipStream_t s)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
         MatDev M{};
         M.state = mats[l].state; M.n = mats[l].n; M.m = mats[l].m;
+        if (dst) M.out = dst[l];
         fill_seed(M, mats[l]);
         md[(size_t)l] = M;
     }
     Plan* p = nullptr;
-    int st = get_plan(kKindTransfer, 0, r, md, s, &p);
+    int st = get_plan(kKindTransfer, dst ? 1 : 0, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = static_cast<const MatDev*>(p->d_table);
     const WorkItem* di2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items2);
     FLORA_HIP(launch_transfer_T(dm, count, r, s));
-    FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, s));
+    FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, ca, cb, s));
     return FLORA_OK;
 }
 
@@ -786,7 +789,23 @@ int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* 
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = transfer_chunk(mats + c0, cn, r, static_cast<hipStream_t>(hip_stream));
+        st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
+    return FLORA_OK;
+}
+
+int flora_transfer_accumulate(const flora_matrix_t* mats, int count, int r, float a, float b,
+                              float* const* dst, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (count > 0 && !dst) return FLORA_ERR_INVALID;
+    for (int l = 0; l < count; ++l)
+        if (!dst[l] || !aligned16(dst[l]) || dst[l] == mats[l].state) return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = transfer_chunk(mats + c0, cn, r, dst + c0, a, b, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;
@@ -818,7 +837,7 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
     const bool next = do_transfer != 0;
     FLORA_FOR_CHUNKS(count, c0, cn) {
         if (next) {
-            st = transfer_chunk(mats + c0, cn, r, s);
+            st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s);
             if (st != FLORA_OK) return st;
         }
         st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, next, s);

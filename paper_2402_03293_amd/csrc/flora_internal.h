@@ -14,7 +14,7 @@ struct MatDev {
     float* col_stat;
     float* vfull;       // n x m second moment of the unfactored rule
     float* wsumsq;      // 1 float: sum of W^2, read for the parameter scale and refreshed by the update
-    void* out;          // flora_decompress destination
+    void* out;          // flora_decompress destination; flora_transfer_accumulate destination (n x r fp32)
     float* T;           // r x r transfer matrix (workspace)
     float* rowpart;     // [ncolchunks][n] partial row sums of Gt^2 (workspace)
     float* colpart;     // [nrowblocks][m] partial column sums of Gt^2 (workspace)
@@ -167,7 +167,8 @@ hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int 
 hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                   int r, int mode, int out_is_bf16, int vec, DecompressParams p, hipStream_t s);
 hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s);
-hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, hipStream_t s);
+hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, float ca, float cb,
+                          hipStream_t s);
 hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);
 hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
                                hipStream_t s);

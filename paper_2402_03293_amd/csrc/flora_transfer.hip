@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void transfer_T_kernel(const MatDev* __restric
 
 template <int R>
 __global__ __launch_bounds__(256) void apply_T_kernel(const MatDev* __restrict__ mats,
-                                                      const WorkItem* __restrict__ items)
+                                                      const WorkItem* __restrict__ items, float ca, float cb)
 {
     constexpr int RP = (R < 16) ? 16 : R;          // rank padded to the MFMA tile
     constexpr int NT2 = RP / 16;
@@ -120,7 +120,11 @@ __global__ __launch_bounds__(256) void apply_T_kernel(const MatDev* __restrict__
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
     const long long n = M.n;
-    float* __restrict__ state = M.state;
+    const float* state = M.state;
+    // destination: the state itself (momentum transfer, ca = 0, cb = 1: every row block is read
+    // into LDS before any of it is written) or another n x r buffer that takes
+    // ca * dst + cb * (state T)
+    float* dst = M.out ? reinterpret_cast<float*>(M.out) : M.state;
     const float* __restrict__ T = M.T;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -161,7 +165,10 @@ __global__ __launch_bounds__(256) void apply_T_kernel(const MatDev* __restrict__
             for (int v = 0; v < 4; ++v) {
                 const long long row = (long long)it.row0 + mtile * 16 + 4 * kg + v;
                 const int k2 = t2 * 16 + li;
-                if (row < n && k2 < R) state[row * R + k2] = acc[b][v];
+                if (row < n && k2 < R) {
+                    const float o = (ca != 0.f) ? dst[row * R + k2] : 0.f;
+                    dst[row * R + k2] = ca * o + cb * acc[b][v];
+                }
             }
         }
     }
@@ -187,17 +194,18 @@ hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s
     return hipGetLastError();
 }
 
-hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, hipStream_t s)
+hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, float ca, float cb,
+                          hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     const dim3 grid((unsigned)nitems), block(256);
     switch (r) {
-    case 8: hipLaunchKernelGGL((apply_T_kernel<8>), grid, block, 0, s, mats, items); break;
-    case 16: hipLaunchKernelGGL((apply_T_kernel<16>), grid, block, 0, s, mats, items); break;
-    case 32: hipLaunchKernelGGL((apply_T_kernel<32>), grid, block, 0, s, mats, items); break;
-    case 64: hipLaunchKernelGGL((apply_T_kernel<64>), grid, block, 0, s, mats, items); break;
-    case 128: hipLaunchKernelGGL((apply_T_kernel<128>), grid, block, 0, s, mats, items); break;
-    case 256: hipLaunchKernelGGL((apply_T_kernel<256>), grid, block, 0, s, mats, items); break;
+    case 8: hipLaunchKernelGGL((apply_T_kernel<8>), grid, block, 0, s, mats, items, ca, cb); break;
+    case 16: hipLaunchKernelGGL((apply_T_kernel<16>), grid, block, 0, s, mats, items, ca, cb); break;
+    case 32: hipLaunchKernelGGL((apply_T_kernel<32>), grid, block, 0, s, mats, items, ca, cb); break;
+    case 64: hipLaunchKernelGGL((apply_T_kernel<64>), grid, block, 0, s, mats, items, ca, cb); break;
+    case 128: hipLaunchKernelGGL((apply_T_kernel<128>), grid, block, 0, s, mats, items, ca, cb); break;
+    case 256: hipLaunchKernelGGL((apply_T_kernel<256>), grid, block, 0, s, mats, items, ca, cb); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

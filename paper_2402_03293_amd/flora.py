@@ -86,6 +86,8 @@ def lib():
         L.flora_decompress.restype = ci
         L.flora_momentum_transfer.argtypes = [MP, ci, ci, vp]
         L.flora_momentum_transfer.restype = ci
+        L.flora_transfer_accumulate.argtypes = [MP, ci, ci, cf, cf, ctypes.POINTER(vp), vp]
+        L.flora_transfer_accumulate.restype = ci
         L.flora_apply_update.argtypes = [MP, ci, ci, ci, ctypes.POINTER(Update), vp]
         L.flora_apply_update.restype = ci
         L.flora_fused_step.argtypes = [MP, ci, ci, ci, ci, cf, cf, ci, ctypes.POINTER(Update), vp]
@@ -119,7 +121,8 @@ def lib():
 
 
 EXPORTS = [
-    "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_apply_update",
+    "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_transfer_accumulate",
+    "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
     "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
     "flora_workspace_bytes", "flora_set_tuning",
@@ -180,6 +183,13 @@ def decompress(mats, r: int, alpha: float, outs, out_dtype: int, stream=None):
 
 def momentum_transfer(mats, r: int, stream=None):
     _check(lib().flora_momentum_transfer(mats, len(mats), r, _stream(stream)), "flora_momentum_transfer")
+
+
+def transfer_accumulate(mats, r: int, a: float, b: float, dsts, stream=None):
+    count = len(mats)
+    arr = (ctypes.c_void_p * count)(*[_ptr(d) for d in dsts])
+    _check(lib().flora_transfer_accumulate(mats, count, r, a, b, arr, _stream(stream)),
+           "flora_transfer_accumulate")
 
 
 def apply_update(mats, r: int, weight_dtype: int, update: Update, stream=None):

@@ -300,6 +300,44 @@ def test_momentum_transfer(n, m, r):
     assert rel_fro(to64(M), ref) < TOL_F32       # fp32 throughout at every rank
 
 
+@pytest.mark.parametrize("n,m,r", [(40, 100, 8), (65, 129, 16), (33, 70, 32), (100, 300, 64),
+                                   (130, 260, 128), (257, 1030, 256)])
+@pytest.mark.parametrize("a,b", [(0.9, 0.1 / 16), (0.0, 1.0), (1.0, -0.5)])
+def test_transfer_accumulate(n, m, r, a, b):
+    # dst <- a dst + b C A_c^T A_m against the literal n x m composition in fp64
+    sc, sm = 4242 + r, 9191 + n
+    C = rand((n, r), sc)
+    M0 = rand((n, r), sm)
+    M = M0.clone()
+    Cc = C.clone()
+    mats = flora.matrices([(n, m)], states=[C], seeds=[sc], seeds_next=[sm])
+    flora.transfer_accumulate(mats, r, a, b, [M])
+    sync()
+    ref = oracle.transfer_accumulate(to64(M0), to64(Cc), m, sc, sm, a, b)
+    assert rel_fro(to64(M), ref) < TOL_F32       # fp32 throughout at every rank
+    assert torch.equal(C, Cc)                     # the source is only read
+
+
+def test_transfer_accumulate_grouped_and_errors():
+    shapes = [(70, 90), (33, 200), (128, 64), (5, 7)]
+    r = 16
+    C = [rand((n, r), 50 + i) for i, (n, m) in enumerate(shapes)]
+    M0 = [rand((n, r), 60 + i) for i, (n, m) in enumerate(shapes)]
+    M = [x.clone() for x in M0]
+    sc = [int(flora.derive_seed(1, l, 0)) for l in range(len(shapes))]
+    sm = [int(flora.derive_seed(2, l, 0)) for l in range(len(shapes))]
+    mats = flora.matrices(shapes, states=C, seeds=sc, seeds_next=sm)
+    flora.transfer_accumulate(mats, r, 0.5, 0.25, M)
+    sync()
+    for l, (n, m) in enumerate(shapes):
+        ref = oracle.transfer_accumulate(to64(M0[l]), to64(C[l]), m, sc[l], sm[l], 0.5, 0.25)
+        assert rel_fro(to64(M[l]), ref) < TOL_F32
+    import ctypes
+    arr = (ctypes.c_void_p * len(shapes))(*[c.data_ptr() for c in C])       # destination = source
+    assert flora.lib().flora_transfer_accumulate(mats, len(shapes), r, 0.5, 0.25, arr, None) == flora.ERR_INVALID
+    assert flora.lib().flora_transfer_accumulate(mats, len(shapes), r, 0.5, 0.25, None, None) == flora.ERR_INVALID
+
+
 # ---------------------------------------------------------------- update
 @pytest.mark.parametrize("n,m,r", [(256, 256, 8), (130, 200, 16), (77, 70, 32), (300, 520, 64), (257, 264, 256)])
 def test_apply_update_sgd(n, m, r):
@@ -475,3 +513,22 @@ def test_more_matrices_than_one_launch_carries_seeds_for():
     sync()
     for l in (0, 447, 448, 499):
         assert rel_fro(to64(outs[l]), oracle.decompress(to64(Ss[l]), m, seeds[l])) < TOL_F32
+
+
+@pytest.mark.parametrize("r,gdt", [(16, "f32"), (64, "bf16")])
+def test_micro_batches_accumulated_straight_into_the_momentum(r, gdt):
+    # one projection for accumulation and momentum: M <- beta M + ((1-beta)/tau) sum_i G_i A, one
+    # compress call per micro-batch, against Algorithm 2's EMA line on the exact mean gradient
+    n, m, tau, beta, seed = 200, 328, 4, 0.9, 321
+    dt = torch.float32 if gdt == "f32" else torch.bfloat16
+    G = [rand((n, m), 700 + i, dtype=dt) for i in range(tau)]
+    M0 = rand((n, r), 710)
+    M = M0.clone()
+    for i in range(tau):
+        mats = flora.matrices([(n, m)], grads=[G[i]], states=[M], seeds=[seed])
+        flora.compress(mats, r, flora.F32 if gdt == "f32" else flora.BF16, beta if i == 0 else 1.0,
+                       (1.0 - beta) / tau)
+    sync()
+    mean = sum(to64(g) for g in G) / tau
+    ref = oracle.compress(mean, r, seed, state=to64(M0), a=beta, b=1.0 - beta)
+    assert rel_fro(to64(M) - beta * to64(M0), ref - beta * to64(M0)) < tol_for(r)

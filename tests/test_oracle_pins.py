@@ -530,3 +530,51 @@ def test_adafactor_step_without_scaling_is_the_factored_rule():
                               scale_parameter=False)
     for x, y in zip(a, b):
         np.testing.assert_array_equal(x, y)
+
+
+# ------------------------------- accumulation feeding momentum (one projection each)
+def test_transfer_accumulate_is_the_matrix_product_it_names():
+    rng = np.random.default_rng(31)
+    n, m, r, a, b = 6, 11, 8, 0.9, 0.025
+    C, M = rng.standard_normal((n, r)), rng.standard_normal((n, r))
+    sc, sm = 1234, 98765
+    Ac, Am = oracle.materialise_A(sc, m, r), oracle.materialise_A(sm, m, r)
+    want = a * M + b * (C @ Ac.T) @ Am
+    got = oracle.transfer_accumulate(M, C, m, sc, sm, a, b)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    # re-associated through the r x r matrix the momentum transfer uses
+    np.testing.assert_allclose(got, a * M + b * oracle.transfer(C, m, sc, sm), rtol=1e-11, atol=1e-13)
+    # swapping the two projections is a different result
+    assert not np.allclose(got, oracle.transfer_accumulate(M, C, m, sm, sc, a, b))
+
+
+def test_algorithm1_output_fed_to_algorithm2_equals_transfer_accumulate():
+    # one optimizer step of "accumulate tau micro-batches (Algorithm 1), then momentum
+    # (Algorithm 2)" written with the n x m intermediate, against the folded form
+    rng = np.random.default_rng(32)
+    n, m, r, tau, beta = 5, 9, 4, 3, 0.9
+    grads = [rng.standard_normal((n, m)) for _ in range(tau)]
+    sc, sm = oracle.derive_seed(5, 0, 1), oracle.derive_seed(6, 0, 1)
+    C = np.zeros((n, r))
+    for G in grads:
+        C = oracle.compress(G, r, sc, state=C)
+    Gt = oracle.decompress(C, m, sc, alpha=1.0 / tau)            # Algorithm 1's output
+    M0 = rng.standard_normal((n, r))
+    M_literal = oracle.compress(Gt, r, sm, state=M0, a=beta, b=1.0 - beta)   # Algorithm 2's EMA line
+    M_folded = oracle.transfer_accumulate(M0, C, m, sc, sm, beta, (1.0 - beta) / tau)
+    np.testing.assert_allclose(M_folded, M_literal, rtol=1e-12, atol=1e-14)
+
+
+def test_accumulating_straight_into_the_momentum_is_algorithm2_on_the_mean_gradient():
+    # With one projection for both, linearity lets the EMA absorb the micro-batches one by
+    # one: M <- beta M + ((1-beta)/tau) G_1 A, then M <- M + ((1-beta)/tau) G_i A, which is
+    # Algorithm 2's EMA line applied to the exact mean gradient.
+    rng = np.random.default_rng(33)
+    n, m, r, tau, beta, seed = 4, 10, 8, 4, 0.8, 77
+    grads = [rng.standard_normal((n, m)) for _ in range(tau)]
+    M0 = rng.standard_normal((n, r))
+    M = M0
+    for i, G in enumerate(grads):
+        M = oracle.compress(G, r, seed, state=M, a=beta if i == 0 else 1.0, b=(1.0 - beta) / tau)
+    want = oracle.compress(sum(grads) / tau, r, seed, state=M0, a=beta, b=1.0 - beta)
+    np.testing.assert_allclose(M, want, rtol=1e-12, atol=1e-14)
