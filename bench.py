@@ -53,6 +53,10 @@ def parse_args():
                          "(beta 0.9) and update from that.  folded: accumulate into C under one projection, "
                          "then M <- beta M + ((1-beta)/tau) C A_c^T A_m (flora_transfer_accumulate); direct: one "
                          "projection for both, every micro-batch is compressed straight into M")
+    ap.add_argument("--layerwise", type=int, default=0, metavar="K",
+                    help="Algorithm-2 workloads only: one flora_fused_step call per K consecutive matrices (the "
+                         "layer-by-layer invocation of an update-in-backward training loop; K = 4 is one "
+                         "transformer block of workloads 3 and 5) instead of one grouped call")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     return ap.parse_args()
@@ -114,6 +118,9 @@ def main():
         col_stats = [torch.zeros((m,), device=dev) for _, m in shapes]
     torch.cuda.synchronize()
 
+    if args.layerwise and wl.algorithm != 2:
+        sys.stderr.write("bench.py: --layerwise applies to the momentum workloads (3, 5)\n")
+        sys.exit(2)
     if args.momentum and wl.algorithm != 1:
         sys.stderr.write("bench.py: --momentum applies to the accumulation workloads (1, 2, 4)\n")
         sys.exit(2)
@@ -133,6 +140,21 @@ def main():
                                 col_stats=col_stats, seeds=seeds, seeds_next=seeds, second_moments=second,
                                 weight_sumsqs=sumsq) for g in range(nsets)]
     views = [flora.fields(mt) for mt in mats_sets]
+    mats_one = None
+    if args.layerwise:
+        # one descriptor per (gradient set, matrix), built once
+        K = args.layerwise
+        groups = [list(range(l0, min(count, l0 + K))) for l0 in range(0, count, K)]
+
+        def pick(xs, idx):
+            return [xs[l] for l in idx] if xs is not None else None
+
+        mats_one = [[flora.matrices(pick(shapes, idx), grads=pick(grad_sets[g], idx), weights=pick(W, idx),
+                                    states=pick(states, idx), row_stats=pick(row_stats, idx),
+                                    col_stats=pick(col_stats, idx), second_moments=pick(second, idx),
+                                    weight_sumsqs=pick(sumsq, idx), seeds=pick(seeds, idx),
+                                    seeds_next=pick(seeds, idx)) for idx in groups]
+                    for g in range(nsets)]
     mats_mom = None
     if args.momentum:
         # descriptors whose state is the momentum: the update reads it; in direct mode the
@@ -180,7 +202,7 @@ def main():
         else:
             upd_mom = flora.sgd_update(wl.lr, 1.0)
 
-    ev_pairs = {"compress": [], "update": [], "transfer": []}
+    ev_pairs = {"compress": [], "update": [], "transfer": [], "layerwise": []}
     record = {"on": False}
 
     def timed(kind, fn):
@@ -246,6 +268,17 @@ def main():
                 timed("transfer", lambda: flora.momentum_transfer(mt, r, stream))
                 seeds = nxt
                 set_seeds(seeds)
+            if args.layerwise:
+                ones = mats_one[tstate["gi"] % nsets]
+                tstate["gi"] += 1
+
+                def all_layers():
+                    for gi in range(len(groups) - 1, -1, -1):  # the order gradients appear in backward
+                        flora.fields(ones[gi])["seed"][:] = seeds[groups[gi][0]:groups[gi][-1] + 1]
+                        flora.fused_step(ones[gi], r, gdt, flora.F32, wl.beta, 1.0 - wl.beta, False, upd, stream)
+                timed("layerwise", all_layers)
+                tstate["t"] += 1
+                return
             mt = mats_sets[tstate["gi"] % nsets]
             tstate["gi"] += 1
             timed("compress", lambda: flora.compress(mt, r, gdt, wl.beta, 1.0 - wl.beta, stream))
@@ -284,9 +317,11 @@ def main():
                    "unfactored": 2 * 4 * S + 20 * E}[rule],
         "transfer": 8 * S if not args.momentum else 12 * S,     # folded: reads C, reads and writes M
     }
+    alg_bytes["layerwise"] = alg_bytes["compress"] + alg_bytes["update"]
     alg_flops = {"compress": 2.0 * E * r,
                  "update": 2.0 * E * r * {"sgd": 1, "factored": 3, "adafactor": 3, "unfactored": 2}[rule],
                  "transfer": sum(2.0 * m * r * r + 2.0 * n * r * r for n, m in shapes)}
+    alg_flops["layerwise"] = alg_flops["compress"] + alg_flops["update"]
     kern = {}
     for k, pairs in ev_pairs.items():
         if not pairs:
@@ -310,7 +345,8 @@ def main():
         pass
     roofline = {
         "kernel": {"compress": "compress (state <- a*state + b*G*A)",
-                   "update": "decompress + update (W <- W - rule(alpha*state*A^T))"}[dominant],
+                   "update": "decompress + update (W <- W - rule(alpha*state*A^T))",
+                   "layerwise": "fused step, one call per %d matrices" % max(1, args.layerwise)}[dominant],
         "bound": "hbm", "achieved": dk["alg_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": dk["alg_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
         "bytes_per_launch": alg_bytes[dominant], "avg_launch_ms": dk["avg_ms"],
@@ -327,7 +363,7 @@ def main():
                    "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
                    "beta": wl.beta if wl.algorithm == 2 else None,
                    "kappa": wl.kappa if wl.algorithm == 2 else None,
-                   "rule": rule, "momentum_from_accumulator": args.momentum, "grad_sets_in_ring": nsets,
+                   "rule": rule, "momentum_from_accumulator": args.momentum, "layerwise": args.layerwise, "grad_sets_in_ring": nsets,
                    "grad_bytes_per_step": grad_bytes_step},
         "roofline": roofline,
         "kernels": kern,

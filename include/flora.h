@@ -33,18 +33,24 @@
  *     gradients are used exactly) and r in {64, 128, 256} (bf16 matrix cores,
  *     fp32 accumulation; bf16 gradients only; A and, when decompressing, the
  *     state are rounded to bf16 on the fly).  Other r: FLORA_ERR_UNSUPPORTED.
- *   - The library keeps a private per-device workspace (descriptor tables,
- *     the r x r transfer matrices, statistic partials, and for small launches
- *     the partial products and arrival counters of row blocks whose columns
- *     are shared between workgroups).  It grows on demand
- *     with hipMalloc the first time a given set of descriptors is seen and is
- *     reused afterwards; flora_shutdown() releases it.  No per-matrix state
- *     (seed, step, epoch) is kept between calls: that lives with the caller.
+ *   - The library keeps private device memory per (set of matrix shapes, stream):
+ *     the work tables of the grouped launches, the r x r transfer matrices,
+ *     statistic partials, for small launches the partial products and arrival
+ *     counters of row blocks whose columns are shared between workgroups, and
+ *     device copies of descriptor tables.  It is allocated with hipMalloc the
+ *     first time a set of shapes is seen on a stream and reused afterwards;
+ *     flora_shutdown() releases it.  A call whose pointers have been seen
+ *     before uploads nothing; one with new pointers (another buffer of a ring,
+ *     a freshly allocated gradient) costs one small asynchronous copy and no
+ *     allocation or synchronisation, so calling once per matrix from a
+ *     training loop stays cheap.  No per-matrix state (seed, step, epoch) is
+ *     kept between calls: that lives with the caller.
  *   - Calls on one stream execute in order.  Calls issued concurrently from
  *     several host threads are serialised by an internal lock.  Two calls on
  *     the same matrices (the same grad / weight / state pointers) must not
  *     run at the same time on different streams: they would race on the
- *     caller's state and on the workspace kept for that set.
+ *     caller's state.  (Workspace is per stream, so calls on different
+ *     matrices of equal shapes may overlap on different streams.)
  *   - Results are bitwise repeatable: every reduction has a fixed order (no
  *     floating-point atomics), also where workgroups combine partial products.
  */

@@ -11,6 +11,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 namespace flora {
@@ -46,14 +47,33 @@ bool rank_bf16(int r) { return r == 64 || r == 128 || r == 256; }
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ------------------------------------------------------------------ plans
+// One uploaded copy of a descriptor table: the caller's pointers (and, for the transfer, seeds)
+// with the plan's workspace pointers and tiling filled in.
+struct Image {
+    std::vector<MatDev> img;     // what the device copy holds
+    uint64_t hash = 0;
+    MatDev* d_mats = nullptr;    // device copy (inside one of the plan's slabs)
+    char* h_stage = nullptr;     // pinned staging of the same size
+    hipEvent_t ev = nullptr;     // recorded after the upload
+    bool ev_pending = false;
+    uint64_t tick = 0;
+};
+
+// Everything that depends only on the shapes of a request (and the stream it runs on): work
+// tables, launch shape, workspace.  Requests that differ in pointers share all of it and own
+// only a descriptor image; an image that has been uploaded before is found by its hash and
+// costs nothing, a new one costs one small asynchronous copy.  Calls that come with new
+// pointers every time (one matrix per call, gradients freshly allocated) therefore neither
+// allocate nor synchronise once the plan exists.
 struct Plan {
     int device = -1;
+    hipStream_t stream = nullptr;
     int kind = -1;
     int count = 0;
     int r = 0;
     int variant = 0;          // compress: 0 fp32 grads, 1 bf16 grads on the fp32 path, 2 bf16 path
-    std::vector<MatDev> host_mats;      // exact copy for collision-proof comparison (device pointers unset)
-    std::vector<MatDev> dev_image;      // what was uploaded (workspace pointers filled in)
+    uint64_t shape_hash = 0;
+    std::vector<MatDev> host_mats;      // shapes and tiling fields (pointers unset)
     std::vector<WorkItem> items;        // main work table
     std::vector<WorkItem> items2;       // transfer: state <- state T table
     int mt = 1;                         // bf16 compress: rows per workgroup = 128 * mt
@@ -61,17 +81,20 @@ struct Plan {
     int kc = 0;                         // fp32 compress: columns per part (0: whole rows)
     size_t ws_floats = 0;               // compress: floats of partial products (shared-column mode)
     size_t ws_counters = 0;             // ... and arrival counters
-    void* d_table = nullptr;            // MatDev[count] + items + items2
-    size_t table_cap = 0;
-    void* d_work = nullptr;             // T / statistic partials
+    void* d_tables = nullptr;           // items + items2 (uploaded once)
+    const WorkItem* d_items = nullptr;
+    const WorkItem* d_items2 = nullptr;
+    void* h_tables = nullptr;           // pinned source of that upload
+    void* d_work = nullptr;             // T / statistic partials / partial products
     size_t work_cap = 0;
-    void* h_pinned = nullptr;
-    size_t pinned_cap = 0;
-    hipEvent_t ev = nullptr;
-    hipStream_t up_stream = nullptr;
-    bool ev_pending = false;
+    size_t mats_bytes = 0;              // size of one descriptor image
+    int image_cap = 16;
+    int images_per_slab = 1;
+    std::vector<void*> dev_slabs, pin_slabs;
+    std::vector<Image> images;
+    std::unordered_multimap<uint64_t, int> index;   // image hash -> slot
+    const MatDev* cur_mats = nullptr;   // the image of the current call
     uint64_t tick = 0;
-    size_t off_items = 0, off_items2 = 0, table_bytes = 0;
 };
 
 // Launch-shape knobs, settable through flora_set_tuning (0 = let the library choose).
@@ -85,16 +108,22 @@ struct Tuning {
 };
 Tuning g_tune;
 
-constexpr int kMaxPlans = 96;
+constexpr int kMaxPlans = 1024;
 std::vector<Plan*> g_plans;
 uint64_t g_tick = 0;
 
 void free_plan(Plan* p)
 {
-    if (p->d_table) (void)hipFree(p->d_table);
+    for (Image& im : p->images) {
+        if (im.ev_pending) (void)hipEventSynchronize(im.ev);
+        if (im.ev) (void)hipEventDestroy(im.ev);
+    }
+    // hipFree waits for the device, so kernels still reading these buffers have finished
+    if (p->d_tables) (void)hipFree(p->d_tables);
     if (p->d_work) (void)hipFree(p->d_work);
-    if (p->h_pinned) (void)hipHostFree(p->h_pinned);
-    if (p->ev) (void)hipEventDestroy(p->ev);
+    for (void* d : p->dev_slabs) (void)hipFree(d);
+    for (void* h : p->pin_slabs) (void)hipHostFree(h);
+    if (p->h_tables) (void)hipHostFree(p->h_tables);
     delete p;
 }
 
@@ -361,122 +390,129 @@ size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r)
     return b;
 }
 
-// How a cached plan relates to a new request with the same (kind, variant, r, count).
-enum Match : int { kExact = 0, kSeedsDiffer = 1, kPointersDiffer = 2, kShapesDiffer = 3 };
-
-Match compare(const Plan& p, const std::vector<MatDev>& mats)
+uint64_t hash_bytes(const void* data, size_t bytes, uint64_t h)
 {
-    Match worst = kExact;
-    for (size_t l = 0; l < mats.size(); ++l) {
-        const MatDev& a = p.host_mats[l];
-        const MatDev& b = mats[l];
-        if (a.n != b.n || a.m != b.m) return kShapesDiffer;
-        if (a.grad != b.grad || a.weight != b.weight || a.state != b.state || a.row_stat != b.row_stat ||
-            a.col_stat != b.col_stat || a.out != b.out || a.vfull != b.vfull || a.wsumsq != b.wsumsq)
-            worst = kPointersDiffer;
-        else if (worst < kSeedsDiffer && (a.seed_lo != b.seed_lo || a.seed_hi != b.seed_hi ||
-                                          a.seedn_lo != b.seedn_lo || a.seedn_hi != b.seedn_hi))
-            worst = kSeedsDiffer;
+    const unsigned char* c = static_cast<const unsigned char*>(data);
+    size_t i = 0;
+    for (; i + 8 <= bytes; i += 8) {
+        uint64_t w;
+        std::memcpy(&w, c + i, 8);
+        h = (h ^ w) * 0x9E3779B97F4A7C15ull;
+        h ^= h >> 29;
     }
-    return worst;
+    for (; i < bytes; ++i) h = (h ^ c[i]) * 0x100000001B3ull;
+    return h;
 }
 
-// Finds or creates the plan for (kind, variant, r, mats) and makes sure its device copy is
-// current on `stream`.  A request that differs from a cached plan only in seeds (a resample)
-// or only in pointers (another buffer of a ring) re-uploads the descriptor table, a few KB;
-// work tables and workspace are rebuilt only when shapes change.
+uint64_t hash_shapes(const std::vector<MatDev>& mats)
+{
+    uint64_t h = 0x243F6A8885A308D3ull;
+    for (const MatDev& M : mats) {
+        const long long nm[2] = {M.n, M.m};
+        h = hash_bytes(nm, sizeof(nm), h);
+    }
+    return h;
+}
+
+bool same_shapes(const Plan& p, const std::vector<MatDev>& mats)
+{
+    for (size_t l = 0; l < mats.size(); ++l)
+        if (p.host_mats[l].n != mats[l].n || p.host_mats[l].m != mats[l].m) return false;
+    return true;
+}
+
+int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
+{
+    const int kind = p->kind, r = p->r, count = p->count;
+    p->host_mats = mats;
+    for (MatDev& M : p->host_mats) {      // shapes only
+        const long long n = M.n, m = M.m;
+        M = MatDev{};
+        M.n = n; M.m = m;
+    }
+    if (kind == kKindCompress) {
+        if (p->variant == 2) build_compress_bf16_items(*p);
+        else build_compress_f32_items(*p);
+    } else if (kind != kKindSumsq) {
+        build_decompress_items(*p);
+        if (kind == kKindTransfer) build_apply_T_items(*p);
+    }
+    const size_t off2 = round_up(sizeof(WorkItem) * p->items.size(), 256);
+    const size_t tbytes = off2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
+    if (tbytes > 0) {
+        FLORA_HIP(hipMalloc(&p->d_tables, tbytes));
+        FLORA_HIP(hipHostMalloc(&p->h_tables, tbytes, hipHostMallocDefault));
+        char* hp = static_cast<char*>(p->h_tables);
+        if (!p->items.empty()) std::memcpy(hp, p->items.data(), sizeof(WorkItem) * p->items.size());
+        if (!p->items2.empty()) std::memcpy(hp + off2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
+        // (the plan is only ever used on this stream, so everything after this copy sees it)
+        FLORA_HIP(hipMemcpyAsync(p->d_tables, p->h_tables, tbytes, hipMemcpyHostToDevice, stream));
+        p->d_items = static_cast<const WorkItem*>(p->d_tables);
+        p->d_items2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_tables) + off2);
+    }
+    size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
+    if (kind == kKindCompress) wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
+    if (wbytes > 0) {
+        FLORA_HIP(hipMalloc(&p->d_work, wbytes));
+        p->work_cap = wbytes;
+        // arrival counters start at zero (the kernel leaves them at zero again)
+        if (kind == kKindCompress && p->ws_counters > 0)
+            FLORA_HIP(hipMemsetAsync(static_cast<char*>(p->d_work) + round_up(p->ws_floats * 4, 256), 0,
+                                     p->ws_counters * 4, stream));
+    }
+    p->mats_bytes = round_up(sizeof(MatDev) * (size_t)count, 256);
+    // descriptor images kept per plan: many for calls on a few matrices (a training loop that
+    // steps one layer per call cycles through hundreds of pointer sets), a few for large sets
+    p->image_cap = count <= 4 ? 512 : (count <= 32 ? 64 : 16);
+    p->images_per_slab = (int)std::max<size_t>(1, std::min<size_t>(64, (64 * 1024) / p->mats_bytes));
+    return FLORA_OK;
+}
+
+// Finds or creates the plan for (kind, variant, r, shapes, stream) and the device copy of this
+// request's descriptor table; p->cur_mats points at it on return.
 int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipStream_t stream, Plan** out)
 {
     int device = 0;
     FLORA_HIP(hipGetDevice(&device));
     const int count = (int)mats.size();
-
-    Plan* best = nullptr;
-    Match best_match = kShapesDiffer;
-    int same_shape_plans = 0;
-    for (Plan* p : g_plans) {
-        if (p->device != device || p->kind != kind || p->variant != variant || p->r != r || p->count != count)
-            continue;
-        const Match mt = compare(*p, mats);
-        if (mt == kShapesDiffer) continue;
-        ++same_shape_plans;
-        if (!best || mt < best_match || (mt == best_match && p->tick < best->tick)) {
-            best = p;
-            best_match = mt;
-        }
-        if (mt == kExact) break;
-    }
-
-    if (best && best_match == kExact) {
-        best->tick = ++g_tick;
-        if (best->ev_pending && best->up_stream != stream) FLORA_HIP(hipStreamWaitEvent(stream, best->ev, 0));
-        *out = best;
-        return FLORA_OK;
-    }
+    const uint64_t sh = hash_shapes(mats);
 
     Plan* p = nullptr;
-    bool keep_tables = false;
-    if (best && (best_match == kSeedsDiffer || same_shape_plans >= 16)) {
-        p = best;            // same shapes: keep its work tables and workspace
-        keep_tables = true;
-    } else {
+    for (Plan* q : g_plans)
+        if (q->shape_hash == sh && q->device == device && q->stream == stream && q->kind == kind &&
+            q->variant == variant && q->r == r && q->count == count && same_shapes(*q, mats)) {
+            p = q;
+            break;
+        }
+    if (!p) {
         if ((int)g_plans.size() >= kMaxPlans) {
             size_t lru = 0;
             for (size_t i = 1; i < g_plans.size(); ++i)
                 if (g_plans[i]->tick < g_plans[lru]->tick) lru = i;
-            if (g_plans[lru]->ev_pending) (void)hipEventSynchronize(g_plans[lru]->ev);
             free_plan(g_plans[lru]);
             g_plans.erase(g_plans.begin() + (long)lru);
         }
         p = new Plan();
+        p->device = device; p->stream = stream; p->kind = kind; p->variant = variant; p->count = count; p->r = r;
+        p->shape_hash = sh;
+        const int st = create_plan(p, mats, stream);
+        if (st != FLORA_OK) {
+            free_plan(p);
+            return st;
+        }
         g_plans.push_back(p);
     }
-    p->device = device; p->kind = kind; p->variant = variant; p->count = count; p->r = r;
     p->tick = ++g_tick;
 
-    if (keep_tables) {
-        for (int l = 0; l < count; ++l) {
-            MatDev M = mats[(size_t)l];
-            const MatDev& old = p->host_mats[(size_t)l];
-            M.ncolchunks = old.ncolchunks; M.nrowblocks = old.nrowblocks; M.item0 = old.item0; M.nitems = old.nitems;
-            p->host_mats[(size_t)l] = M;
-        }
-    } else {
-        p->host_mats = mats;
-        p->items.clear();
-        p->items2.clear();
-        if (kind == kKindCompress) {
-            if (variant == 2) build_compress_bf16_items(*p);
-            else build_compress_f32_items(*p);
-        } else if (kind != kKindSumsq) {
-            build_decompress_items(*p);
-            if (kind == kKindTransfer) build_apply_T_items(*p);
-        }
-        p->off_items = round_up(sizeof(MatDev) * (size_t)count, 256);
-        p->off_items2 = p->off_items + round_up(sizeof(WorkItem) * p->items.size(), 256);
-        p->table_bytes = p->off_items2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
-        size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
-        if (kind == kKindCompress) wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
-        if (p->d_work) { (void)hipFree(p->d_work); p->d_work = nullptr; }
-        if (wbytes > 0) {
-            FLORA_HIP(hipMalloc(&p->d_work, wbytes));
-            p->work_cap = wbytes;
-            // arrival counters start at zero (the kernel leaves them at zero again)
-            if (kind == kKindCompress && p->ws_counters > 0)
-                FLORA_HIP(hipMemsetAsync(static_cast<char*>(p->d_work) + round_up(p->ws_floats * 4, 256), 0,
-                                         p->ws_counters * 4, stream));
-        }
-        FLORA_HIP(hipMalloc(&p->d_table, p->table_bytes));
-        p->table_cap = p->table_bytes;
-        FLORA_HIP(hipHostMalloc(&p->h_pinned, p->table_bytes, hipHostMallocDefault));
-        p->pinned_cap = p->table_bytes;
-        FLORA_HIP(hipEventCreateWithFlags(&p->ev, hipEventDisableTiming));
-    }
-
-    p->dev_image = p->host_mats;
+    // this request's image: the caller's pointers, the plan's tiling and workspace
+    static thread_local std::vector<MatDev> img;
+    img = mats;
     {
         char* w = static_cast<char*>(p->d_work);
-        for (MatDev& M : p->dev_image) {
+        for (int l = 0; l < count; ++l) {
+            MatDev& M = img[(size_t)l];
+            const MatDev& t = p->host_mats[(size_t)l];
+            M.ncolchunks = t.ncolchunks; M.nrowblocks = t.nrowblocks; M.item0 = t.item0; M.nitems = t.nitems;
             if (kind == kKindTransfer) { M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256); }
             if (kind == kKindFactored) {
                 M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * M.n * 4, 256);
@@ -486,21 +522,62 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
             }
         }
     }
-
-    // The pinned staging copy may still be the source of the previous upload.
-    if (p->ev_pending) { FLORA_HIP(hipEventSynchronize(p->ev)); p->ev_pending = false; }
-    char* hp = static_cast<char*>(p->h_pinned);
-    std::memcpy(hp, p->dev_image.data(), sizeof(MatDev) * (size_t)count);
-    size_t upload = sizeof(MatDev) * (size_t)count;
-    if (!keep_tables) {
-        if (!p->items.empty()) std::memcpy(hp + p->off_items, p->items.data(), sizeof(WorkItem) * p->items.size());
-        if (!p->items2.empty()) std::memcpy(hp + p->off_items2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
-        upload = p->table_bytes;
+    const size_t ibytes = sizeof(MatDev) * (size_t)count;
+    const uint64_t h = hash_bytes(img.data(), ibytes, 0x13198A2E03707344ull);
+    auto range = p->index.equal_range(h);
+    for (auto it = range.first; it != range.second; ++it) {
+        Image& im = p->images[(size_t)it->second];
+        if (std::memcmp(im.img.data(), img.data(), ibytes) == 0) {
+            im.tick = g_tick;
+            p->cur_mats = im.d_mats;
+            *out = p;
+            return FLORA_OK;
+        }
     }
-    FLORA_HIP(hipMemcpyAsync(p->d_table, p->h_pinned, upload, hipMemcpyHostToDevice, stream));
-    FLORA_HIP(hipEventRecord(p->ev, stream));
-    p->ev_pending = true;
-    p->up_stream = stream;
+
+    int slot = -1;
+    if ((int)p->images.size() < p->image_cap) {
+        slot = (int)p->images.size();
+        const int slab = slot / p->images_per_slab, within = slot % p->images_per_slab;
+        if (slab >= (int)p->dev_slabs.size()) {
+            void* d = nullptr;
+            void* hp = nullptr;
+            FLORA_HIP(hipMalloc(&d, p->mats_bytes * (size_t)p->images_per_slab));
+            p->dev_slabs.push_back(d);
+            FLORA_HIP(hipHostMalloc(&hp, p->mats_bytes * (size_t)p->images_per_slab, hipHostMallocDefault));
+            p->pin_slabs.push_back(hp);
+        }
+        Image im;
+        im.d_mats = reinterpret_cast<MatDev*>(static_cast<char*>(p->dev_slabs[(size_t)slab]) + p->mats_bytes * (size_t)within);
+        im.h_stage = static_cast<char*>(p->pin_slabs[(size_t)slab]) + p->mats_bytes * (size_t)within;
+        FLORA_HIP(hipEventCreateWithFlags(&im.ev, hipEventDisableTiming));
+        p->images.push_back(std::move(im));
+    } else {
+        // every slot is taken: the least recently used image gives way.  Kernels that read its
+        // device copy were enqueued on this stream before the copy below; its staging buffer may
+        // still be the source of its previous upload.
+        slot = 0;
+        for (size_t i = 1; i < p->images.size(); ++i)
+            if (p->images[i].tick < p->images[(size_t)slot].tick) slot = (int)i;
+        Image& old = p->images[(size_t)slot];
+        auto rg = p->index.equal_range(old.hash);
+        for (auto it = rg.first; it != rg.second; ++it)
+            if (it->second == slot) {
+                p->index.erase(it);
+                break;
+            }
+        if (old.ev_pending) { FLORA_HIP(hipEventSynchronize(old.ev)); old.ev_pending = false; }
+    }
+    Image& im = p->images[(size_t)slot];
+    im.img = img;
+    im.hash = h;
+    im.tick = g_tick;
+    std::memcpy(im.h_stage, img.data(), ibytes);
+    FLORA_HIP(hipMemcpyAsync(im.d_mats, im.h_stage, ibytes, hipMemcpyHostToDevice, stream));
+    FLORA_HIP(hipEventRecord(im.ev, stream));
+    im.ev_pending = true;
+    p->index.emplace(h, slot);
+    p->cur_mats = im.d_mats;
     *out = p;
     return FLORA_OK;
 }
@@ -563,8 +640,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     Plan* p = nullptr;
     int st = get_plan(kKindCompress, variant, r, md, s, &p);
     if (st != FLORA_OK) return st;
-    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
-    const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
+    const MatDev* dm = p->cur_mats;
+    const WorkItem* di = p->d_items;
     if (variant == 2) {
         float* partials = static_cast<float*>(p->d_work);
         uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
@@ -588,8 +665,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
 static int run_decompress(Plan* p, const SeedArgs& sa, int r, int mode, int out_bf16, DecompressParams dp,
                           hipStream_t s)
 {
-    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
-    const WorkItem* di = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items);
+    const MatDev* dm = p->cur_mats;
+    const WorkItem* di = p->d_items;
     if (rank_bf16(r)) FLORA_HIP(launch_decompress_bf16(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, p->vec, dp, s));
     else FLORA_HIP(launch_decompress_f32(dm, di, (int)p->items.size(), sa, r, mode, out_bf16, dp, s));
     return FLORA_OK;
@@ -628,8 +705,8 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* c
     Plan* p = nullptr;
     int st = get_plan(kKindTransfer, dst ? 1 : 0, r, md, s, &p);
     if (st != FLORA_OK) return st;
-    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
-    const WorkItem* di2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_table) + p->off_items2);
+    const MatDev* dm = p->cur_mats;
+    const WorkItem* di2 = p->d_items2;
     FLORA_HIP(launch_transfer_T(dm, count, r, s));
     FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, ca, cb, s));
     return FLORA_OK;
@@ -658,7 +735,7 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, const flor
     const int kind = (factored || unfactored) ? kKindFactored : kKindDecompress;
     int st = get_plan(kind, unfactored ? 3 : 2, r, md, s, &p);
     if (st != FLORA_OK) return st;
-    const MatDev* dm = static_cast<const MatDev*>(p->d_table);
+    const MatDev* dm = p->cur_mats;
     if (u->rule == FLORA_RULE_SGD) {
         DecompressParams dp{u->alpha, u->lr * u->alpha, 0.f, 0.f};
         st = run_decompress(p, sa, r, kModeSgd, 0, dp, s);
@@ -700,7 +777,7 @@ static int sumsq_chunk(const flora_matrix_t* mats, int count, hipStream_t s)
     Plan* p = nullptr;
     int st = get_plan(kKindSumsq, 0, 0, md, s, &p);
     if (st != FLORA_OK) return st;
-    FLORA_HIP(launch_weight_sumsq(static_cast<const MatDev*>(p->d_table), count, static_cast<float*>(p->d_work), s));
+    FLORA_HIP(launch_weight_sumsq(p->cur_mats, count, static_cast<float*>(p->d_work), s));
     return FLORA_OK;
 }
 
@@ -950,10 +1027,7 @@ int flora_set_tuning(const char* name, int value)
         return FLORA_ERR_INVALID;
     }
     // cached work tables were built for the old shapes
-    for (Plan* p : g_plans) {
-        if (p->ev_pending) (void)hipEventSynchronize(p->ev);
-        free_plan(p);
-    }
+    for (Plan* p : g_plans) free_plan(p);
     g_plans.clear();
     return FLORA_OK;
 }
@@ -974,10 +1048,7 @@ const char* flora_status_string(int status)
 void flora_shutdown(void)
 {
     std::lock_guard<std::mutex> guard(g_lock);
-    for (Plan* p : g_plans) {
-        if (p->ev_pending) (void)hipEventSynchronize(p->ev);
-        free_plan(p);
-    }
+    for (Plan* p : g_plans) free_plan(p);
     g_plans.clear();
 }
 

@@ -1,0 +1,161 @@
+"""The torch.optim-shaped front end, grouped and layer by layer (a hook per parameter steps a
+weight as soon as its gradient exists), against the oracle's drivers of Algorithm 1 and
+Algorithm 2.  Gradients are seeded and synthetic and reach the optimizer through autograd:
+the loss sum_l <W_l, G_l> has gradient G_l exactly, whatever the weights are, so the oracle
+can be fed the same sequence without reading anything back from the GPU."""
+import numpy as np
+import pytest
+
+import oracle
+
+torch = pytest.importorskip("torch")
+from paper_2402_03293_amd import flora, optim  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SHAPES = [(96, 160), (64, 200), (130, 72)]
+
+
+def to64(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def rel_fro(x, ref):
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(np.asarray(x) - ref) / (den if den > 0 else 1.0))
+
+
+def make_params(seed, bf16_grads):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    ps = []
+    for s in SHAPES:
+        p = torch.nn.Parameter((0.1 * torch.randn(*s, generator=g)).to(DEV))
+        if bf16_grads:
+            p.grad_dtype = torch.bfloat16
+        ps.append(p)
+    return ps
+
+
+def make_grads(steps, seed, bf16):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    out = []
+    for _ in range(steps):
+        gs = [torch.randn(*s, generator=g) for s in SHAPES]
+        if bf16:
+            gs = [x.to(torch.bfloat16).to(torch.float32) for x in gs]     # exactly representable in bf16
+        out.append([x.to(DEV) for x in gs])
+    return out
+
+
+def backward_with(params, grads):
+    loss = sum((p * g).sum() for p, g in zip(params, grads))
+    loss.backward()
+
+
+@pytest.mark.parametrize("layerwise", [False, True])
+@pytest.mark.parametrize("r,bf16", [(16, False), (64, True)])
+def test_momentum_sgd_with_resampling(r, bf16, layerwise):
+    beta, kappa, lr, steps, gseed = 0.9, 3, 0.05, 7, 11
+    params = make_params(1, bf16)
+    W0 = [to64(p) for p in params]
+    grads = make_grads(steps, 2, bf16)
+    opt = optim.Flora(params, r, lr, beta=beta, kappa=kappa, rule="sgd", seed=gseed)
+    if layerwise:
+        opt.attach()
+    for t in range(steps):
+        backward_with(params, grads[t])
+        if layerwise:
+            assert all(p.grad is None for p in params)        # consumed and released inside backward
+        else:
+            opt.step()
+            opt.zero_grad()
+    torch.cuda.synchronize()
+    ref = oracle.Algorithm2(SHAPES, r, beta, kappa, gseed)
+    W = W0
+    for t in range(steps):
+        _, W = ref.step([to64(g) for g in grads[t]], W, lr=lr)
+    assert ref.transfers == 3 * len(SHAPES)                   # t = 0, 3, 6
+    tol = 1e-5 if r <= 32 else 2e-2
+    for l in range(len(SHAPES)):
+        assert rel_fro(to64(opt.state[l]), ref.M[l]) < tol
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < max(tol, 3e-5)
+        assert opt.seed[l] == ref.seed[l] and opt.updates[l] == steps
+
+
+@pytest.mark.parametrize("layerwise", [False, True])
+@pytest.mark.parametrize("rule", ["sgd", "adafactor"])
+def test_accumulation_cycles(rule, layerwise):
+    r, tau, cycles, gseed = 16, 3, 2, 5
+    params = make_params(3, False)
+    W = [to64(p) for p in params]
+    W0 = [w.copy() for w in W]
+    grads = make_grads(tau * cycles, 4, False)
+    opt = optim.Flora(params, r, 0.05 if rule == "sgd" else None, tau=tau, rule=rule, seed=gseed)
+    if layerwise:
+        opt.attach()
+    for i in range(tau * cycles):
+        backward_with(params, grads[i])
+        if not layerwise:
+            opt.step()
+            opt.zero_grad()
+    torch.cuda.synchronize()
+    fac = dict(R=[np.zeros(n) for n, _ in SHAPES], K=[np.zeros(m) for _, m in SHAPES], eps1=1e-30, eps2=1e-3,
+               clip_d=1.0, scale_parameter=True)
+    for c in range(cycles):
+        gsteps = [[to64(g) for g in grads[c * tau + i]] for i in range(tau)]
+        if rule == "sgd":
+            W, _, _ = oracle.algorithm1_cycle(W, gsteps, r, gseed, c, 0.05)
+        else:
+            fac["step"], fac["beta2"] = oracle.adafactor_schedule(c + 1)
+            W, _, _ = oracle.algorithm1_cycle(W, gsteps, r, gseed, c, 0.0, rule="adafactor", factored=fac)
+    for l in range(len(SHAPES)):
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < 1e-4
+        assert float(opt.state[l].abs().max()) == 0.0          # reset at the end of the cycle
+        assert opt.updates[l] == cycles and opt.epoch[l] == cycles
+
+
+def test_micro_batches_into_momentum_and_unfactored_rule():
+    # tau micro-batches compressed straight into the momentum, unfactored Adafactor on its yield,
+    # layer by layer; against Algorithm 2 on the cycle's mean gradient
+    r, tau, beta, kappa, updates, gseed = 32, 2, 0.8, 2, 3, 9
+    params = make_params(5, False)
+    W = [to64(p) for p in params]
+    W0 = [w.copy() for w in W]
+    grads = make_grads(tau * updates, 6, False)
+    opt = optim.Flora(params, r, 0.01, tau=tau, beta=beta, kappa=kappa, rule="unfactored", seed=gseed,
+                      scale_parameter=False)
+    for l, (n, m) in enumerate(SHAPES):
+        opt.second[l].fill_(float(m) / r)                      # resumed from a typical second moment
+    opt.attach()
+    for i in range(tau * updates):
+        backward_with(params, grads[i])
+    torch.cuda.synchronize()
+    ref = oracle.Algorithm2(SHAPES, r, beta, kappa, gseed)
+    V = [np.full(s, float(s[1]) / r) for s in SHAPES]
+    for u in range(updates):
+        mean = [sum(to64(grads[u * tau + i][l]) for i in range(tau)) / tau for l in range(len(SHAPES))]
+        ys, _ = ref.step(mean)
+        _, beta2 = oracle.adafactor_schedule(u + 1)
+        for l in range(len(SHAPES)):
+            W[l], V[l] = oracle.adafactor_step(W[l], ys[l], V=V[l], beta2=beta2, eps1=1e-30, clip_d=1.0,
+                                               step=0.01, scale_parameter=False)
+    for l in range(len(SHAPES)):
+        assert rel_fro(to64(opt.state[l]), ref.M[l]) < 1e-5
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < 1e-4
+        assert rel_fro(to64(opt.second[l]), V[l]) < 1e-4
+
+
+def test_front_end_rejects_what_the_library_cannot_take():
+    p1 = torch.nn.Parameter(torch.zeros(8, device=DEV))
+    with pytest.raises(ValueError):
+        optim.Flora([p1], 16, 0.1)
+    p2 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV, dtype=torch.bfloat16))
+    with pytest.raises(ValueError):
+        optim.Flora([p2], 16, 0.1)
+    with pytest.raises(ValueError):
+        optim.Flora([torch.nn.Parameter(torch.zeros((8, 8), device=DEV))], 16, None, rule="sgd")
+    p3 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV))
+    opt = optim.Flora([p3], 64, 0.1)
+    p3.grad = torch.zeros((8, 8), device=DEV)                  # fp32 gradient at a bf16-path rank
+    with pytest.raises(flora.FloraError):
+        opt.step()
