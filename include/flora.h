@@ -184,6 +184,17 @@ void flora_adafactor_schedule(uint64_t t, float* rho, float* beta2);
 int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t* raw_out,
                          void* hip_stream);
 
+/* Test hook, host only (touches no GPU): the table of workgroups the library would launch for
+ * this set of shapes.  kind 0: flora_compress, 1: flora_decompress and the update passes,
+ * 2: the state <- state T pass of the transfer.  Returns the number of workgroups (or a
+ * negative flora_status_t) and writes up to `cap` of them to `out`, 12 int64 each:
+ * matrix, first row, rows, first column, rank slice (compress) or column chunk (decompress),
+ * row-block index, end column, part, number of parts, arrival counter, offset of the partial
+ * products in the workspace (floats), 0.  info (5 int64, may be NULL): rows-per-workgroup code,
+ * vector-kernel flag, columns per part, floats of partial products, arrival counters. */
+int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, int r,
+                               flora_dtype_t grad_dtype, int64_t* out, int64_t cap, int64_t* info);
+
 /* Measurement hook: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 16;
  * both DEVICE pointers 16-byte aligned, not overlapping).  Profiler byte counters for the
  * hot-path kernels are scaled by what they read for this copy of known size. */

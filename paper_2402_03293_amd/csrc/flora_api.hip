@@ -959,6 +959,44 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
     return FLORA_OK;
 }
 
+int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, int r,
+                               flora_dtype_t grad_dtype, int64_t* out, int64_t cap, int64_t* info)
+{
+    if (count < 0 || (count > 0 && !mats) || kind < 0 || kind > 2) return FLORA_ERR_INVALID;
+    if (!rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
+    for (int l = 0; l < count; ++l)
+        if (mats[l].n < 1 || mats[l].m < 1 || mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24))
+            return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    Plan p;
+    p.count = count; p.r = r;
+    p.host_mats.resize((size_t)count);
+    for (int l = 0; l < count; ++l) { p.host_mats[(size_t)l].n = mats[l].n; p.host_mats[(size_t)l].m = mats[l].m; }
+    if (kind == 0) {
+        p.kind = kKindCompress;
+        p.variant = rank_bf16(r) ? 2 : (grad_dtype == FLORA_BF16 ? 1 : 0);
+        if (p.variant == 2) build_compress_bf16_items(p);
+        else build_compress_f32_items(p);
+    } else {
+        p.kind = kind == 1 ? kKindDecompress : kKindTransfer;
+        build_decompress_items(p);
+        if (kind == 2) build_apply_T_items(p);
+    }
+    const std::vector<WorkItem>& items = (kind == 2) ? p.items2 : p.items;
+    if (info) {
+        info[0] = p.mt; info[1] = p.vec; info[2] = p.kc;
+        info[3] = (int64_t)p.ws_floats; info[4] = (int64_t)p.ws_counters;
+    }
+    if (out)
+        for (size_t i = 0; i < items.size() && (int64_t)i < cap; ++i) {
+            const WorkItem& w = items[i];
+            int64_t* o = out + 12 * i;
+            o[0] = w.mat; o[1] = w.row0; o[2] = w.rows; o[3] = w.col0; o[4] = w.slice; o[5] = w.rblock;
+            o[6] = w.col1; o[7] = w.part; o[8] = w.nparts; o[9] = w.cidx; o[10] = w.poff; o[11] = 0;
+        }
+    return (int64_t)items.size();
+}
+
 int flora_debug_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
 {
     if (!src || !dst || !aligned16(src) || !aligned16(dst) || (bytes % 16) != 0) return FLORA_ERR_INVALID;

@@ -98,6 +98,8 @@ def lib():
         L.flora_adafactor_schedule.restype = None
         L.flora_debug_generate.argtypes = [ctypes.c_uint64, ctypes.c_int64, ci, vp, vp, vp]
         L.flora_debug_generate.restype = ci
+        L.flora_debug_work_items.argtypes = [ci, MP, ci, ci, ci, vp, ctypes.c_int64, vp]
+        L.flora_debug_work_items.restype = ctypes.c_int64
         L.flora_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.flora_debug_copy.restype = ci
         L.flora_derive_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
@@ -124,7 +126,7 @@ EXPORTS = [
     "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_transfer_accumulate",
     "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
-    "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
+    "flora_debug_work_items", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
     "flora_workspace_bytes", "flora_set_tuning",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
@@ -206,6 +208,21 @@ def fused_step(mats, r: int, grad_dtype: int, weight_dtype: int, a: float, b: fl
 def debug_generate(seed: int, m: int, r: int, A_out=None, raw_out=None, stream=None):
     _check(lib().flora_debug_generate(seed, m, r, _ptr(A_out), _ptr(raw_out), _stream(stream)),
            "flora_debug_generate")
+
+
+def debug_work_items(kind: int, shapes, r: int, grad_dtype: int = F32):
+    """(items, info): the work table for these shapes as an int64 array [workgroups, 12] and the
+    launch-shape info (host only, no GPU).  Columns: mat, row0, rows, col0, slice, rblock, col1,
+    part, nparts, cidx, poff, 0."""
+    import numpy as np
+    mats = matrices(shapes)
+    info = np.zeros(5, dtype=np.int64)
+    n = lib().flora_debug_work_items(kind, mats, len(mats), r, grad_dtype, None, 0, info.ctypes.data)
+    if n < 0:
+        raise FloraError(int(n), "flora_debug_work_items")
+    out = np.zeros((int(n), 12), dtype=np.int64)
+    lib().flora_debug_work_items(kind, mats, len(mats), r, grad_dtype, out.ctypes.data, int(n), info.ctypes.data)
+    return out, info
 
 
 def debug_copy(src, dst, nbytes: int, stream=None):
