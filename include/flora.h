@@ -31,8 +31,10 @@
  *     FLORA_ERR_UNSUPPORTED nothing has been launched.
  *   - Supported ranks: r in {8, 16, 32} (fp32 matrix cores; fp32 or bf16
  *     gradients are used exactly) and r in {64, 128, 256} (bf16 matrix cores,
- *     fp32 accumulation; bf16 gradients only; A and, when decompressing, the
- *     state are rounded to bf16 on the fly).  Other r: FLORA_ERR_UNSUPPORTED.
+ *     fp32 accumulation; A and, when decompressing, the state are rounded to
+ *     bf16 on the fly; bf16 gradients are used exactly and take the fastest
+ *     kernel, fp32 gradients are rounded to bf16, nearest even, in registers).
+ *     Other r: FLORA_ERR_UNSUPPORTED.
  *   - The library keeps private device memory per (set of matrix shapes, stream):
  *     the work tables of the grouped launches, the r x r transfer matrices,
  *     statistic partials, for small launches the partial products and arrival

@@ -71,7 +71,8 @@ struct Plan {
     int kind = -1;
     int count = 0;
     int r = 0;
-    int variant = 0;          // compress: 0 fp32 grads, 1 bf16 grads on the fp32 path, 2 bf16 path
+    int variant = 0;          // compress: 0 fp32 grads, 1 bf16 grads on the fp32 path, 2 bf16 path,
+                              // 3 bf16 path with fp32 grads (rounded in registers)
     uint64_t shape_hash = 0;
     std::vector<MatDev> host_mats;      // shapes and tiling fields (pointers unset)
     std::vector<WorkItem> items;        // main work table
@@ -188,7 +189,7 @@ void build_compress_bf16_items(Plan& p)
     // bytes of extra traffic per block, so parts stay at 768 columns or more.
     // Unaligned sets take the narrow kernel with the largest rows-per-workgroup (128 * mt)
     // that still gives the chip two workgroups per compute unit.
-    bool aligned = true;
+    bool aligned = p.variant != 3;      // fp32 gradients take the narrow kernel
     for (int l = 0; l < p.count; ++l)   // 16-byte aligned rows, 32-bit byte offsets within 64 rows
         aligned = aligned && (p.host_mats[l].m % 8) == 0 && p.host_mats[l].m <= (1LL << 23);
     const int wide_slice = (p.r == 64) ? 64 : 128;
@@ -202,7 +203,7 @@ void build_compress_bf16_items(Plan& p)
     };
     int mt = 4;
     long long kc = 0;       // columns per part (0: whole rows)
-    if (g_tune.compress_bf16_mt) {
+    if (g_tune.compress_bf16_mt && (aligned || g_tune.compress_bf16_mt <= 4)) {
         mt = g_tune.compress_bf16_mt;
         kc = g_tune.compress_splitk_cols;
     } else if (aligned) {
@@ -431,7 +432,7 @@ int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
         M.n = n; M.m = m;
     }
     if (kind == kKindCompress) {
-        if (p->variant == 2) build_compress_bf16_items(*p);
+        if (p->variant >= 2) build_compress_bf16_items(*p);
         else build_compress_f32_items(*p);
     } else if (kind != kKindSumsq) {
         build_decompress_items(*p);
@@ -636,18 +637,19 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     }
     SeedArgs sa;
     fill_seed_args(sa, mats, count, use_next);
-    const int variant = rank_bf16(r) ? 2 : (grad_dtype == FLORA_BF16 ? 1 : 0);
+    const int variant = rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : (grad_dtype == FLORA_BF16 ? 1 : 0);
     Plan* p = nullptr;
     int st = get_plan(kKindCompress, variant, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = p->cur_mats;
     const WorkItem* di = p->d_items;
-    if (variant == 2) {
+    if (variant >= 2) {
         float* partials = static_cast<float*>(p->d_work);
         uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
                                                                    round_up(p->ws_floats * 4, 256))
                                        : nullptr;
-        FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, a, b, partials, counters, s));
+        FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, variant == 3, a, b, partials,
+                                          counters, s));
     }
     else {
         // column groups per workgroup: two for whole rows; one when the pieces are 512 columns
@@ -788,7 +790,6 @@ static int check_grads(const flora_matrix_t* mats, int count, int r, flora_dtype
     for (int l = 0; l < count; ++l)
         if (!mats[l].grad || !aligned16(mats[l].grad) || mats[l].grad == (const void*)mats[l].state)
             return FLORA_ERR_INVALID;
-    if (rank_bf16(r) && grad_dtype != FLORA_BF16) return FLORA_ERR_UNSUPPORTED;
     return FLORA_OK;
 }
 
@@ -974,8 +975,8 @@ int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, 
     for (int l = 0; l < count; ++l) { p.host_mats[(size_t)l].n = mats[l].n; p.host_mats[(size_t)l].m = mats[l].m; }
     if (kind == 0) {
         p.kind = kKindCompress;
-        p.variant = rank_bf16(r) ? 2 : (grad_dtype == FLORA_BF16 ? 1 : 0);
-        if (p.variant == 2) build_compress_bf16_items(p);
+        p.variant = rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : (grad_dtype == FLORA_BF16 ? 1 : 0);
+        if (p.variant >= 2) build_compress_bf16_items(p);
         else build_compress_f32_items(p);
     } else {
         p.kind = kind == 1 ? kKindDecompress : kKindTransfer;

@@ -1,8 +1,9 @@
-// Compression on the bf16 matrix cores, ranks 64 / 128 / 256, bf16 gradients:
+// Compression on the bf16 matrix cores, ranks 64 / 128 / 256:
 //     state <- a * state + b * (G A(seed))
 // (Algorithm 1, compression line; Algorithm 2, EMA line).  A is rounded to
 // bf16 as it is generated; products are exact in fp32 and accumulated in fp32
-// (v_mfma_f32_32x32x16_bf16).
+// (v_mfma_f32_32x32x16_bf16).  G is bf16, or fp32 rounded to bf16 (nearest even)
+// in registers on its way to the matrix cores (first kernel below only).
 //
 // The cost that matters here is regenerating A, not the contraction: every
 // workgroup that sweeps the m columns of G must rebuild all the A rows it
@@ -27,7 +28,7 @@ constexpr int kBK = 32;            // columns of G per tile
 constexpr int kLda = kBK + 8;      // padded LDS row (bf16 elements): 80 bytes
 constexpr int kRS = kCompressBf16Slice;
 
-template <int MT>
+template <int MT, typename GT>
 __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __restrict__ mats,
                                                             const WorkItem* __restrict__ items,
                                                             const SeedArgs seeds, int R, float a, float b)
@@ -39,19 +40,20 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
     const MatDev& M = mats[it.mat];
     const long long n = M.n, m = M.m;
     const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
-    const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(M.grad);
+    const GT* __restrict__ G = reinterpret_cast<const GT*>(M.grad);
     float* __restrict__ state = M.state;
+    constexpr bool kF32 = sizeof(GT) == 4;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, g = lane >> 5;
     const float cgen = neg2_ln2_over(R);
-    const bool vec_ok = (m % 8) == 0;
+    const bool vec_ok = (m % (kF32 ? 4 : 8)) == 0;   // rows start on 16-byte boundaries
     const int ntiles = (int)((m + kBK - 1) / kBK);
     const int nfull = vec_ok ? (int)(m / kBK) : 0;
     const int q0 = it.slice * (kRS / 4);   // first Philox quad of this rank slice
 
-    const uint16_t* rowp[MT];
+    const GT* rowp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         long long row = (long long)it.row0 + wave * (MT * 32) + mt * 32 + li;
@@ -59,13 +61,30 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
         rowp[mt] = G + row * m;
     }
 
+    // element c of the row as bf16 bits (zero past the end)
+    auto elem = [&](const GT* rp, long long c) -> uint32_t {
+        if (c >= m) return 0u;
+        if constexpr (kF32) return f32_to_bf16_bits(ldg(reinterpret_cast<const float*>(rp) + c));
+        else return ldg(reinterpret_cast<const uint16_t*>(rp) + c);
+    };
+
     auto load_tile = [&](v4u (&dst)[MT][2], int tile) {
         const long long j0 = (long long)tile * kBK + 16 * g;
         if (tile < nfull) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                dst[mt][0] = ldg4(rowp[mt] + j0);
-                dst[mt][1] = ldg4(rowp[mt] + j0 + 8);
+                if constexpr (kF32) {
+                    const float* rp = reinterpret_cast<const float*>(rowp[mt]) + j0;
+                    const v4f f0 = ldg4(rp), f1 = ldg4(rp + 4), f2 = ldg4(rp + 8), f3 = ldg4(rp + 12);
+                    dst[mt][0] = v4u{pack_bf16x2(f0.x, f0.y), pack_bf16x2(f0.z, f0.w),
+                                     pack_bf16x2(f1.x, f1.y), pack_bf16x2(f1.z, f1.w)};
+                    dst[mt][1] = v4u{pack_bf16x2(f2.x, f2.y), pack_bf16x2(f2.z, f2.w),
+                                     pack_bf16x2(f3.x, f3.y), pack_bf16x2(f3.z, f3.w)};
+                } else {
+                    const uint16_t* rp = reinterpret_cast<const uint16_t*>(rowp[mt]) + j0;
+                    dst[mt][0] = ldg4(rp);
+                    dst[mt][1] = ldg4(rp + 8);
+                }
             }
         } else {
 #pragma unroll
@@ -74,9 +93,7 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const long long c0 = j0 + 2 * e;
-                    const uint32_t lo = (c0 < m) ? ldg(rowp[mt] + c0) : 0u;
-                    const uint32_t hi = (c0 + 1 < m) ? ldg(rowp[mt] + c0 + 1) : 0u;
-                    w[e] = lo | (hi << 16);
+                    w[e] = elem(rowp[mt], c0) | (elem(rowp[mt], c0 + 1) << 16);
                 }
                 dst[mt][0] = v4u{w[0], w[1], w[2], w[3]};
                 dst[mt][1] = v4u{w[4], w[5], w[6], w[7]};
@@ -431,11 +448,12 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
 // kernel), chosen by the host.  partials / counters: workspace of the wide kernel's shared-column
 // mode (may be null when no item has nparts > 1).
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
-                                   const SeedArgs& seeds, int r, int mt, float a, float b, float* partials,
-                                   uint32_t* counters, hipStream_t s)
+                                   const SeedArgs& seeds, int r, int mt, int grad_is_f32, float a, float b,
+                                   float* partials, uint32_t* counters, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
+    if (grad_is_f32 && mt > 4) return hipErrorInvalidValue;   // fp32 gradients: first kernel only
     if (mt == 8 || mt == 16) {   // wide kernel: 512 (8) or 256 (16) rows per workgroup, rank slices of 128 (64 at r = 64)
         const dim3 grid((unsigned)nitems), block(512);
         if (mt == 8) {
@@ -449,9 +467,18 @@ hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, in
     }
     const dim3 grid((unsigned)nitems), block(256);
     switch (mt) {
-    case 1: hipLaunchKernelGGL((compress_bf16_kernel<1>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
-    case 2: hipLaunchKernelGGL((compress_bf16_kernel<2>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
-    case 4: hipLaunchKernelGGL((compress_bf16_kernel<4>), grid, block, 0, s, mats, items, seeds, r, a, b); break;
+    case 1:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<1, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<1, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
+    case 2:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<2, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<2, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
+    case 4:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<4, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<4, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

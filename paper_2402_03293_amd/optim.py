@@ -18,8 +18,8 @@ Schedules follow the paper's two algorithms:
   gradient of the cycle.
 
 Only 2-D fp32 parameters are accepted (the paper projects the attention and feed-forward weight
-matrices); ranks 8/16/32 take fp32 or bf16 gradients, ranks 64/128/256 bf16 gradients (set
-``param.grad_dtype = torch.bfloat16`` to have autograd produce them).
+matrices).  Gradients may be fp32 or bf16 at every rank; at ranks 64/128/256 bf16 gradients take
+the fastest kernel (``param.grad_dtype = torch.bfloat16`` makes autograd produce them).
 """
 from __future__ import annotations
 

@@ -56,7 +56,6 @@ def test_compress_validation():
     assert L.flora_compress(ok, 1, 0, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(ok, 1, 12, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(ok, 1, 512, flora.BF16, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
-    assert L.flora_compress(ok, 1, 64, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(ok, 1, 16, 7, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(_mats(n=0), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(_mats(m=-3), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
@@ -100,8 +99,8 @@ def test_update_validation():
         == flora.ERR_INVALID
     now = flora.matrices([(16, 16)], states=[0x3000], seeds=[1])
     assert L.flora_apply_update(now, 1, 16, flora.F32, ctypes.byref(sgd), None) == flora.ERR_INVALID
-    assert L.flora_fused_step(ok, 1, 64, flora.F32, flora.F32, 0.9, 0.1, 0, ctypes.byref(sgd), None) \
-        == flora.ERR_UNSUPPORTED
+    assert L.flora_fused_step(ok, 1, 64, flora.F32, flora.BF16, 0.9, 0.1, 0, ctypes.byref(sgd), None) \
+        == flora.ERR_UNSUPPORTED            # bf16 weights
     assert L.flora_fused_step(ok, 0, 64, flora.BF16, flora.F32, 0.9, 0.1, 0, ctypes.byref(sgd), None) == flora.OK
 
 

@@ -155,7 +155,7 @@ def test_front_end_rejects_what_the_library_cannot_take():
     with pytest.raises(ValueError):
         optim.Flora([torch.nn.Parameter(torch.zeros((8, 8), device=DEV))], 16, None, rule="sgd")
     p3 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV))
-    opt = optim.Flora([p3], 64, 0.1)
-    p3.grad = torch.zeros((8, 8), device=DEV)                  # fp32 gradient at a bf16-path rank
+    opt = optim.Flora([p3], 48, 0.1)                           # a rank the library has no kernel for
+    p3.grad = torch.zeros((8, 8), device=DEV)
     with pytest.raises(flora.FloraError):
         opt.step()

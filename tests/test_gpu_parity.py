@@ -138,6 +138,30 @@ def test_compress_bf16_path(n, m, r):
     assert e < 6e-3          # one bf16-rounded operand: about 2^-9 / sqrt(3)
 
 
+# fp32 gradients at the bf16-path ranks: rounded to bf16 in registers, same bar as bf16 gradients
+@pytest.mark.parametrize("mt", [0, 1, 2, 4])
+@pytest.mark.parametrize("n,m,r", [(300, 520, 64), (257, 1001, 128), (1100, 264, 256), (70, 36, 256), (513, 31, 64)])
+def test_compress_bf16_path_fp32_gradients(n, m, r, mt):
+    seed = 2500 + n + m + r
+    G = rand((n, m), seed)
+    S0 = rand((n, r), seed + 1)
+    st = S0.clone()
+    st2 = torch.zeros((n, r), device=DEV)
+    flora.set_tuning("compress_bf16_mt", mt)
+    try:
+        flora.compress(flora.matrices([(n, m)], grads=[G], states=[st], seeds=[seed]), r, flora.F32, 0.9, 0.1)
+        flora.compress(flora.matrices([(n, m)], grads=[G], states=[st2], seeds=[seed]), r, flora.F32, 1.0, 1.0)
+        sync()
+    finally:
+        flora.set_tuning("compress_bf16_mt", 0)
+    assert rel_fro(to64(st), oracle.compress(to64(G), r, seed, state=to64(S0), a=0.9, b=0.1)) < TOL_BF16
+    e = rel_fro(to64(st2), oracle.compress(to64(G), r, seed))
+    assert e < TOL_BF16 and e < 8e-3, e          # two bf16-rounded operands
+    # rounding G first and multiplying exactly is what the kernel does: against that it is tight
+    Gb = to64(G.to(torch.bfloat16))
+    assert rel_fro(to64(st2), oracle.compress(Gb, r, seed)) < 6e-3
+
+
 # every launch shape of the bf16 compress kernel, forced through the tuning hook: the narrow
 # kernel (128 / 256 / 512 rows per workgroup) and the wide one (8 / 16: 512 / 256 rows, rank slices
 # of 128),
@@ -486,7 +510,7 @@ def test_error_codes_launch_nothing():
     L = flora.lib()
     mats = flora.matrices([(n, m)], grads=[G], states=[S], seeds=[1])
     assert L.flora_compress(mats, 1, 12, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
-    assert L.flora_compress(mats, 1, 64, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_compress(mats, 1, 512, flora.BF16, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(mats, -1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(mats, 0, 16, flora.F32, 1.0, 1.0, None) == flora.OK
     bad = flora.matrices([(n, m)], grads=[G.data_ptr() + 4], states=[S], seeds=[1])
