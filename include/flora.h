@@ -188,7 +188,9 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
 
 /* Test hook, host only (touches no GPU): the table of workgroups the library would launch for
  * this set of shapes.  kind 0: flora_compress, 1: flora_decompress and the update passes,
- * 2: the state <- state T pass of the transfer.  Returns the number of workgroups (or a
+ * 2: the state <- state T pass of the transfer, 3: its T = A^T A' pass (ranks 64 and above; a
+ * workgroup takes columns [first column, end column) of chunk `part` and slab `rank slice` of
+ * the rows of T).  Returns the number of workgroups (or a
  * negative flora_status_t) and writes up to `cap` of them to `out`, 12 int64 each:
  * matrix, first row, rows, first column, rank slice (compress) or column chunk (decompress),
  * row-block index, end column, part, number of parts, arrival counter, offset of the partial

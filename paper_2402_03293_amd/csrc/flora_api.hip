@@ -365,13 +365,35 @@ void build_decompress_items(Plan& p)
 
 void build_apply_T_items(Plan& p)
 {
+    const int rows = p.r >= 64 ? kApplyTRowsBig : kApplyTRows;
     for (int l = 0; l < p.count; ++l) {
         const long long n = p.host_mats[l].n;
-        for (long long r0 = 0; r0 < n; r0 += kApplyTRows) {
+        for (long long r0 = 0; r0 < n; r0 += rows) {
             WorkItem w{};
-            w.mat = l; w.row0 = (int)r0; w.rows = (int)std::min<long long>(kApplyTRows, n - r0);
+            w.mat = l; w.row0 = (int)r0; w.rows = (int)std::min<long long>(rows, n - r0);
             p.items2.push_back(w);
         }
+    }
+}
+
+// T = A_old^T A_new at ranks 64 and above: (matrix, chunk of 1024 columns, slab of up to 128 rows
+// of T); ncolchunks of the matrix = its number of chunks (the partials the combine pass adds).
+void build_transfer_T_items(Plan& p)
+{
+    if (p.r < 64) return;
+    const int slabs = p.r / std::min(p.r, 128);
+    for (int l = 0; l < p.count; ++l) {
+        const long long m = p.host_mats[l].m;
+        const int chunks = (int)((m + kTransferChunk - 1) / kTransferChunk);
+        p.host_mats[l].ncolchunks = chunks;
+        for (int c = 0; c < chunks; ++c)
+            for (int s = 0; s < slabs; ++s) {
+                WorkItem w{};
+                w.mat = l; w.slice = s; w.part = c;
+                w.col0 = (int)((long long)c * kTransferChunk);
+                w.col1 = (int)std::min<long long>(m, (long long)(c + 1) * kTransferChunk);
+                p.items.push_back(w);
+            }
     }
 }
 
@@ -379,7 +401,10 @@ size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r)
 {
     size_t b = 0;
     for (const MatDev& M : mats) {
-        if (kind == kKindTransfer) b += round_up((size_t)r * r * 4, 256);
+        if (kind == kKindTransfer) {
+            b += round_up((size_t)r * r * 4, 256);
+            if (r >= 64) b += round_up((size_t)M.ncolchunks * r * r * 4, 256);
+        }
         if (kind == kKindFactored) {
             b += round_up((size_t)M.ncolchunks * M.n * 4, 256);
             b += round_up((size_t)M.nrowblocks * M.m * 4, 256);
@@ -434,9 +459,11 @@ int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
     if (kind == kKindCompress) {
         if (p->variant >= 2) build_compress_bf16_items(*p);
         else build_compress_f32_items(*p);
+    } else if (kind == kKindTransfer) {
+        build_transfer_T_items(*p);
+        build_apply_T_items(*p);
     } else if (kind != kKindSumsq) {
         build_decompress_items(*p);
-        if (kind == kKindTransfer) build_apply_T_items(*p);
     }
     const size_t off2 = round_up(sizeof(WorkItem) * p->items.size(), 256);
     const size_t tbytes = off2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
@@ -514,7 +541,10 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
             MatDev& M = img[(size_t)l];
             const MatDev& t = p->host_mats[(size_t)l];
             M.ncolchunks = t.ncolchunks; M.nrowblocks = t.nrowblocks; M.item0 = t.item0; M.nitems = t.nitems;
-            if (kind == kKindTransfer) { M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256); }
+            if (kind == kKindTransfer) {
+                M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256);
+                if (r >= 64) { M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * r * r * 4, 256); }
+            }
             if (kind == kKindFactored) {
                 M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * M.n * 4, 256);
                 M.colpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.nrowblocks * M.m * 4, 256);
@@ -709,7 +739,7 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* c
     if (st != FLORA_OK) return st;
     const MatDev* dm = p->cur_mats;
     const WorkItem* di2 = p->d_items2;
-    FLORA_HIP(launch_transfer_T(dm, count, r, s));
+    FLORA_HIP(launch_transfer_T(dm, p->d_items, (int)p->items.size(), count, r, s));
     FLORA_HIP(launch_apply_T(dm, di2, (int)p->items2.size(), r, ca, cb, s));
     return FLORA_OK;
 }
@@ -963,7 +993,7 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
 int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, int r,
                                flora_dtype_t grad_dtype, int64_t* out, int64_t cap, int64_t* info)
 {
-    if (count < 0 || (count > 0 && !mats) || kind < 0 || kind > 2) return FLORA_ERR_INVALID;
+    if (count < 0 || (count > 0 && !mats) || kind < 0 || kind > 3) return FLORA_ERR_INVALID;
     if (!rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
     for (int l = 0; l < count; ++l)
         if (mats[l].n < 1 || mats[l].m < 1 || mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24))
@@ -980,8 +1010,9 @@ int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, 
         else build_compress_f32_items(p);
     } else {
         p.kind = kind == 1 ? kKindDecompress : kKindTransfer;
-        build_decompress_items(p);
-        if (kind == 2) build_apply_T_items(p);
+        if (kind == 1) build_decompress_items(p);
+        else if (kind == 2) build_apply_T_items(p);
+        else build_transfer_T_items(p);
     }
     const std::vector<WorkItem>& items = (kind == 2) ? p.items2 : p.items;
     if (info) {
@@ -1035,7 +1066,12 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
         items += (size_t)M.nitems;
         md[(size_t)l] = M;
     }
-    return workspace_bytes_for(md, kKindTransfer, r) + workspace_bytes_for(md, kKindFactored, r) +
+    size_t transfer = 0;
+    for (const MatDev& M : md) {
+        transfer += round_up((size_t)r * r * 4, 256);
+        if (r >= 64) transfer += round_up((size_t)((M.m + kTransferChunk - 1) / kTransferChunk) * r * r * 4, 256);
+    }
+    return transfer + workspace_bytes_for(md, kKindFactored, r) +
            sizeof(MatDev) * (size_t)count + sizeof(WorkItem) * items;
 }
 

@@ -16,7 +16,7 @@ struct MatDev {
     float* wsumsq;      // 1 float: sum of W^2, read for the parameter scale and refreshed by the update
     void* out;          // flora_decompress destination; flora_transfer_accumulate destination (n x r fp32)
     float* T;           // r x r transfer matrix (workspace)
-    float* rowpart;     // [ncolchunks][n] partial row sums of Gt^2 (workspace)
+    float* rowpart;     // [ncolchunks][n] partial row sums of Gt^2; transfer: [chunks][r][r] partials of T (workspace)
     float* colpart;     // [nrowblocks][m] partial column sums of Gt^2 (workspace)
     float* itempart;    // [nitems] per-workgroup partial sums of U^2, later of the new W^2 (workspace)
     float* scal;        // [4]: mean(R), clip scale, parameter scale max(eps2, RMS(W)) or 1, spare (workspace)
@@ -166,7 +166,7 @@ hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int 
                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);
 hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                   int r, int mode, int out_is_bf16, int vec, DecompressParams p, hipStream_t s);
-hipError_t launch_transfer_T(const MatDev* mats, int count, int r, hipStream_t s);
+hipError_t launch_transfer_T(const MatDev* mats, const WorkItem* items, int nitems, int count, int r, hipStream_t s);
 hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, float ca, float cb,
                           hipStream_t s);
 hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);
@@ -182,7 +182,9 @@ constexpr int kCompressBf16Slice = 64;   // rank columns per workgroup, bf16 com
 constexpr int kDecompressCols = 128;     // columns per workgroup, 4-byte-per-lane decompress kernels
 constexpr int kDecompressColsVec = 256;  // columns per workgroup, 16-byte-per-lane bf16 decompress kernel
 constexpr int kDecompressRows = 256;     // rows per workgroup, both decompress kernels
-constexpr int kApplyTRows = 32;          // rows per workgroup, state <- state T
+constexpr int kApplyTRows = 32;          // rows per workgroup, state <- state T, ranks below 64
+constexpr int kApplyTRowsBig = 64;       // ... ranks 64 and above
+constexpr int kTransferChunk = 1024;     // columns per workgroup of the T kernel, ranks 64 and above
 constexpr int kSumsqBlocks = 256;        // workgroups per matrix, sum of W^2
 
 }  // namespace flora

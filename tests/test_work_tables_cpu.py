@@ -127,9 +127,23 @@ def test_transfer_row_blocks(shapes, r):
         its = sorted((it[1], it[2]) for it in items if it[0] == l)
         pos = 0
         for row0, rows in its:
-            assert row0 == pos and 1 <= rows <= 32
+            assert row0 == pos and 1 <= rows <= (64 if r >= 64 else 32)
             pos += rows
         assert pos == n
+    # T = A^T A' at ranks 64 and above: every slab of rows of T sees every column exactly once
+    titems, _ = flora.debug_work_items(3, shapes, r)
+    if r < 64:
+        assert len(titems) == 0
+        return
+    slabs = r // min(r, 128)
+    for l, (n, m) in enumerate(shapes):
+        for s_ in range(slabs):
+            its = sorted((it[7], it[3], it[6]) for it in titems if it[0] == l and it[4] == s_)
+            pos = 0
+            for c, (part, col0, col1) in enumerate(its):
+                assert part == c and col0 == pos and col0 < col1 <= col0 + 1024
+                pos = col1
+            assert pos == m
 
 
 @pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
