@@ -424,20 +424,46 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     const rsrc_t prs = make_rsrc(gbase, (long long)it.nparts * BR * RS * 4);
     const long long rows_here = row_end - it.row0;          // valid rows of the block
     const int nvec = (int)rows_here * (RS / 4);
-    for (int f = tid; f < nvec; f += 512) {
-        const int row = f / (RS / 4), c4 = f % (RS / 4);
-        v4f sum = {0.f, 0.f, 0.f, 0.f};
-        for (int q = 0; q < it.nparts; ++q) {
-            // device-coherent load: the other parts were written by other compute units
-            const v4f pv = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(
-                prs, (int)(((uint32_t)q * (BR * RS) + (uint32_t)row * RS + 4u * (uint32_t)c4) * 4u), 0, 16));
-            sum.x += pv.x; sum.y += pv.y; sum.z += pv.z; sum.w += pv.w;
+    // Two float4 positions per thread and four parts at a time are fetched before any is added,
+    // so the combine costs a few memory round trips, not one per part and position; a part or
+    // a position that does not exist is pointed out of range and adds exact zeros.  The order
+    // of the additions stays 0 .. nparts - 1.
+    const rsrc_t srs = make_rsrc(state + (long long)it.row0 * R, rows_here * (long long)R * 4);
+    for (int f0 = tid; f0 < nvec; f0 += 2 * 512) {
+        uint32_t poff2[2], soff[2];
+        v4f oldv[2], sum[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int f = f0 + 512 * u;
+            const bool ok = f < nvec;
+            const int row = f / (RS / 4), c4 = f % (RS / 4);
+            poff2[u] = ok ? ((uint32_t)row * RS + 4u * (uint32_t)c4) * 4u : kOob;
+            soff[u] = ok ? ((uint32_t)row * (uint32_t)R + (uint32_t)(it.slice * RS) + 4u * (uint32_t)c4) * 4u : kOob;
+            oldv[u] = (a != 0.f) ? buf_load_f4(srs, soff[u]) : v4f{0.f, 0.f, 0.f, 0.f};
+            sum[u] = v4f{0.f, 0.f, 0.f, 0.f};
         }
-        float* sp = state + ((long long)it.row0 + row) * R + it.slice * RS + 4 * c4;
-        v4f o = {0.f, 0.f, 0.f, 0.f};
-        if (a != 0.f) o = ldg4(sp);
-        *(FLORA_GLOBAL v4f*)sp = v4f{a * o.x + b * sum.x, a * o.y + b * sum.y,
-                                                        a * o.z + b * sum.z, a * o.w + b * sum.w};
+        for (int q0 = 0; q0 < it.nparts; q0 += 4) {
+            v4f pv[4][2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    // device-coherent load: the other parts were written by other compute units
+                    const bool ok = q0 + j < it.nparts && poff2[u] != kOob;
+                    const uint32_t off = ok ? (uint32_t)(q0 + j) * (uint32_t)(BR * RS * 4) + poff2[u] : kOob;
+                    pv[j][u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(prs, (int)off, 0, 16));
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    sum[u].x += pv[j][u].x; sum[u].y += pv[j][u].y; sum[u].z += pv[j][u].z; sum[u].w += pv[j][u].w;
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            buf_store_f4(srs, soff[u], v4f{a * oldv[u].x + b * sum[u].x, a * oldv[u].y + b * sum[u].y,
+                                           a * oldv[u].z + b * sum[u].z, a * oldv[u].w + b * sum[u].w});
     }
     if (tid == 0) counters[it.cidx] = 0u;     // every part has arrived: ready for the next launch
 }

@@ -278,15 +278,41 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         const rsrc_t prs = make_rsrc(partials + (size_t)it.poff, (long long)it.nparts * ROWS * RP * 4);
         long long rows_here = n - it.row0;
         rows_here = rows_here > it.rows ? it.rows : rows_here;
-        for (int f = tg; f < (int)rows_here * R; f += 256) {
-            const int row = f / R, k = f % R;
-            float sum = 0.f;
-            for (int q = 0; q < it.nparts; ++q)
-                sum += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                           prs, (int)(((uint32_t)q * (ROWS * RP) + (uint32_t)row * RP + (uint32_t)k) * 4u), 0, 16));
-            float* sp = state + ((long long)it.row0 + row) * R + k;
-            const float o = (a != 0.f) ? ldg(sp) : 0.f;
-            stg(sp, a * o + b * sum);
+        // Four entries per thread and four parts at a time are fetched before any is added, so
+        // the combine costs a few memory round trips, not one per part and entry; a part or an
+        // entry that does not exist is pointed out of range and adds an exact zero.  The order
+        // of the additions stays 0 .. nparts - 1.
+        const int total = (int)rows_here * R;
+        const rsrc_t srs = make_rsrc(state + (long long)it.row0 * R, (long long)total * 4);
+        for (int f0 = tg; f0 < total; f0 += 4 * 256) {
+            uint32_t poff4[4], soff[4];
+            float oldv[4], sum[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int f = f0 + 256 * u;
+                const bool ok = f < total;
+                poff4[u] = ok ? ((uint32_t)(f / R) * RP + (uint32_t)(f % R)) * 4u : kOob;
+                soff[u] = ok ? (uint32_t)f * 4u : kOob;
+                oldv[u] = (a != 0.f) ? buf_load_f(srs, soff[u]) : 0.f;
+                sum[u] = 0.f;
+            }
+            for (int q0 = 0; q0 < it.nparts; q0 += 4) {
+                float pv[4][4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const bool ok = q0 + j < it.nparts && poff4[u] != kOob;
+                        const uint32_t off = ok ? (uint32_t)(q0 + j) * (uint32_t)(ROWS * RP * 4) + poff4[u] : kOob;
+                        pv[j][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(prs, (int)off, 0, 16));
+                    }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) sum[u] += pv[j][u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) buf_store_f(srs, soff[u], a * oldv[u] + b * sum[u]);
         }
         if (tg == 0) counters[it.cidx] = 0u;   // every part has arrived: ready for the next launch
         return;
