@@ -45,8 +45,11 @@
  *     before uploads nothing; one with new pointers (another buffer of a ring,
  *     a freshly allocated gradient) costs one small asynchronous copy and no
  *     allocation or synchronisation, so calling once per matrix from a
- *     training loop stays cheap.  No per-matrix state (seed, step, epoch) is
- *     kept between calls: that lives with the caller.
+ *     training loop stays cheap.  A call whose shapes and pointers have been
+ *     seen on its stream is kernel launches only, so it may be recorded into a
+ *     HIP graph (seeds are kernel arguments: a resample means a new capture or
+ *     a node update).  No per-matrix state (seed, step, epoch) is kept between
+ *     calls: that lives with the caller.
  *   - Calls on one stream execute in order.  Calls issued concurrently from
  *     several host threads are serialised by an internal lock.  Two calls on
  *     the same matrices (the same grad / weight / state pointers) must not
