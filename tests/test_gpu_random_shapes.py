@@ -1,0 +1,71 @@
+"""Seeded random shapes through every entry point against the oracle: ragged rows and columns,
+single rows and columns, widths around every tile size the kernels use, several matrices per
+launch, all six ranks, both gradient types."""
+import numpy as np
+import pytest
+
+import oracle
+
+torch = pytest.importorskip("torch")
+from paper_2402_03293_amd import flora  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RANKS = [8, 16, 32, 64, 128, 256]
+EDGES = [1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
+         767, 768, 1023, 1025]
+
+
+def to64(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def rel_fro(x, ref):
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(np.asarray(x) - ref) / (den if den > 0 else 1.0))
+
+
+def draw_shapes(rng, count):
+    out = []
+    for _ in range(count):
+        n = int(rng.choice(EDGES)) if rng.random() < 0.7 else int(rng.integers(1, 700))
+        m = int(rng.choice(EDGES)) if rng.random() < 0.7 else int(rng.integers(1, 1300))
+        out.append((n, m))
+    return out
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shape_sets(case):
+    rng = np.random.default_rng(1000 + case)
+    r = RANKS[case % 6]
+    bf16 = bool((case // 6) % 2) or r >= 64 and case % 4 != 3       # fp32 gradients at high ranks now and then
+    shapes = draw_shapes(rng, int(rng.integers(1, 5)))
+    tol = 1e-5 if r <= 32 else 2e-2
+    g = torch.Generator(device="cpu").manual_seed(case)
+    gdt = torch.bfloat16 if bf16 else torch.float32
+    G = [torch.randn(*s, generator=g).to(gdt).to(DEV) for s in shapes]
+    S0 = [torch.randn(n, r, generator=g).to(DEV) for n, _ in shapes]
+    W0 = [torch.randn(*s, generator=g).to(DEV) for s in shapes]
+    seeds = [int(flora.derive_seed(case, l, 0)) for l in range(len(shapes))]
+    seeds2 = [int(flora.derive_seed(case, l, 1)) for l in range(len(shapes))]
+    # every entry point starts from the same seeded state, so each is checked on its own
+    Sc, Sd, St = ([x.clone() for x in S0] for _ in range(3))
+    W = [x.clone() for x in W0]
+    out = [torch.full(s, float("nan"), device=DEV) for s in shapes]
+    a, b, alpha, lr = 0.75, 0.5, 0.25, 0.1
+    flora.compress(flora.matrices(shapes, grads=G, states=Sc, seeds=seeds), r, flora.BF16 if bf16 else flora.F32, a, b)
+    md = flora.matrices(shapes, weights=W, states=Sd, seeds=seeds)
+    flora.decompress(md, r, alpha, out, flora.F32)
+    flora.apply_update(md, r, flora.F32, flora.sgd_update(lr, alpha))
+    flora.momentum_transfer(flora.matrices(shapes, states=St, seeds=seeds, seeds_next=seeds2), r)
+    torch.cuda.synchronize()
+    for l, (n, m) in enumerate(shapes):
+        ref = oracle.compress(to64(G[l]), r, seeds[l], state=to64(S0[l]), a=a, b=b)
+        assert rel_fro(to64(Sc[l]), ref) < tol, ("compress", shapes[l], r)
+        Gt = oracle.decompress(to64(S0[l]), m, seeds[l], alpha=alpha)
+        assert rel_fro(to64(out[l]), Gt) < tol, ("decompress", shapes[l], r)
+        assert not torch.isnan(out[l]).any()
+        assert torch.equal(Sd[l], S0[l])
+        assert rel_fro(to64(W[l]) - to64(W0[l]), -lr * Gt) < max(tol, 3e-5), ("update", shapes[l], r)
+        Tr = oracle.transfer(to64(S0[l]), m, seeds[l], seeds2[l])
+        assert rel_fro(to64(St[l]), Tr) < 2e-5, ("transfer", shapes[l], r)

@@ -183,7 +183,13 @@ def test_workload4_accumulate_and_factored_update():
         worst_c = max(worst_c, rel_fro(to64(C[l][idx]), Cl))
     assert worst_c < TOL_BF16 and worst_c < 8e-3, worst_c
 
-    C_whole = {l: to64(C[l]) for l in whole}
+    # the oracle's own accumulators of the whole matrices (all tau micro-steps in fp64)
+    C_whole = {}
+    for l in whole:
+        Cl = np.zeros((wl.shapes[l][0], r))
+        for i in range(tau):
+            Cl = oracle.compress(to64(Gsets[i % 2][l]), r, int(seeds[l]), state=Cl)
+        C_whole[l] = Cl
     upd = flora.factored_update(wl.lr, 1.0 / tau, ex["beta2"], ex["eps1"], ex["clip_d"], zero_state_after=True)
     flora.apply_update(flora.matrices(wl.shapes, weights=W, states=C, row_stats=R, col_stats=K, seeds=seeds),
                        r, flora.F32, upd)
@@ -191,7 +197,6 @@ def test_workload4_accumulate_and_factored_update():
     worst_u = worst_s = 0.0
     for l in whole:
         n, m = wl.shapes[l]
-        # the oracle continues from the GPU's own accumulator: this isolates the update
         Gt = oracle.decompress(C_whole[l], m, int(seeds[l]), alpha=1.0 / tau)
         Wr, Rr, Kr = oracle.factored_update(W0[l], Gt, np.zeros(n), np.zeros(m), ex["beta2"], ex["eps1"],
                                             ex["clip_d"], wl.lr)
