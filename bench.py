@@ -181,7 +181,7 @@ def main():
         return mk(rho, alpha_u, beta2, 1e-30, 1.0, zero_state_after=zero_after, scale_parameter=True, eps2=1e-3)
 
     if rule in ("adafactor", "unfactored"):
-        flora.weight_sumsq(mats_sets[0], stream)     # once: the updates carry it from here on
+        flora.weight_sumsq(mats_sets[0], flora.F32, stream)     # once: the updates carry it from here on
         upd = adafactor_update(1)
     elif wl.rule == "factored":
         ex = wl.extra

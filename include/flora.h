@@ -83,7 +83,7 @@ typedef enum {
 /* One weight matrix.  Fields a given call does not use may be NULL / 0. */
 typedef struct flora_matrix {
     const void* grad;      /* device, n x m row-major, fp32 or bf16; read only                            */
-    void*       weight;    /* device, n x m row-major fp32; read-modify-write by the update calls        */
+    void*       weight;    /* device, n x m row-major, fp32 or bf16; read-modify-write by the update calls */
     float*      state;     /* device, n x r row-major fp32: C (Algorithm 1) or M (Algorithm 2)           */
     float*      row_stat;  /* device, n floats: factored rule's row second moment R, else NULL           */
     float*      col_stat;  /* device, m floats: factored rule's column second moment K, else NULL        */
@@ -162,7 +162,8 @@ int flora_transfer_accumulate(const flora_matrix_t* mats, int count, int r, floa
  *   again for it.  lr and beta2 for step t of the published schedules:
  *   flora_adafactor_schedule.
  * Uses weight, state, n, m, seed (+ row_stat, col_stat | second_moment, + weight_sumsq).
- * weight_dtype must be FLORA_F32. */
+ * weight_dtype: FLORA_F32, or FLORA_BF16 (the update is computed in fp32 from the bf16 weights
+ * and rounded to nearest even when stored; the sum of squares is that of the stored values). */
 int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
                        const flora_update_t* u, void* hip_stream);
 
@@ -176,7 +177,7 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
 
 /* weight_sumsq[0] <- sum of W^2 for every matrix (one read of W; fixed summation order).
  * Uses weight, weight_sumsq, n, m. */
-int flora_weight_sumsq(const flora_matrix_t* mats, int count, void* hip_stream);
+int flora_weight_sumsq(const flora_matrix_t* mats, int count, flora_dtype_t weight_dtype, void* hip_stream);
 
 /* Host-side helper: Adafactor's published schedules for step t = 1, 2, ... (t = 0 is read
  * as 1): relative step size *rho = min(1e-2, 1/sqrt(t)) and second-moment decay

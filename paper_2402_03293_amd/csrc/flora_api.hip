@@ -744,8 +744,8 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* c
     return FLORA_OK;
 }
 
-static int update_chunk(const flora_matrix_t* mats, int count, int r, const flora_update_t* u, bool use_next,
-                        hipStream_t s)
+static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16, const flora_update_t* u,
+                        bool use_next, hipStream_t s)
 {
     const bool factored = u->rule == FLORA_RULE_FACTORED, unfactored = u->rule == FLORA_RULE_UNFACTORED;
     const bool scaled = (factored || unfactored) && u->scale_parameter != 0;
@@ -753,7 +753,7 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, const flor
     bool any_sumsq = false;
     for (int l = 0; l < count; ++l) {
         MatDev M{};
-        M.weight = static_cast<float*>(mats[l].weight); M.state = mats[l].state;
+        M.weight = mats[l].weight; M.state = mats[l].state;
         M.n = mats[l].n; M.m = mats[l].m;
         if (factored) { M.row_stat = mats[l].row_stat; M.col_stat = mats[l].col_stat; }
         if (unfactored) M.vfull = mats[l].second_moment;
@@ -765,12 +765,12 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, const flor
     fill_seed_args(sa, mats, count, use_next);
     Plan* p = nullptr;
     const int kind = (factored || unfactored) ? kKindFactored : kKindDecompress;
-    int st = get_plan(kind, unfactored ? 3 : 2, r, md, s, &p);
+    int st = get_plan(kind, (unfactored ? 3 : 2) + (wbf16 ? 4 : 0), r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = p->cur_mats;
     if (u->rule == FLORA_RULE_SGD) {
         DecompressParams dp{u->alpha, u->lr * u->alpha, 0.f, 0.f};
-        st = run_decompress(p, sa, r, kModeSgd, 0, dp, s);
+        st = run_decompress(p, sa, r, kModeSgd, wbf16, dp, s);
         if (st != FLORA_OK) return st;
     } else {
         DecompressParams dp{u->alpha, u->lr, u->beta2, u->eps1};
@@ -788,7 +788,7 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, const flor
         }
         // clip factor from the partial sums of U^2; parameter scale from the caller's sum of W^2
         FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, scaled ? 1 : 0, u->eps2, s));
-        st = run_decompress(p, sa, r, factored ? kModeFactored : kModeFull2, 0, dp, s);
+        st = run_decompress(p, sa, r, factored ? kModeFactored : kModeFull2, wbf16, dp, s);
         if (st != FLORA_OK) return st;
         // the update pass left per-workgroup sums of the new W^2
         if (any_sumsq) FLORA_HIP(launch_wsumsq_finalize(dm, count, s));
@@ -797,19 +797,19 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, const flor
     return FLORA_OK;
 }
 
-static int sumsq_chunk(const flora_matrix_t* mats, int count, hipStream_t s)
+static int sumsq_chunk(const flora_matrix_t* mats, int count, int wbf16, hipStream_t s)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
         MatDev M{};
-        M.weight = static_cast<float*>(mats[l].weight); M.wsumsq = mats[l].weight_sumsq;
+        M.weight = mats[l].weight; M.wsumsq = mats[l].weight_sumsq;
         M.n = mats[l].n; M.m = mats[l].m;
         md[(size_t)l] = M;
     }
     Plan* p = nullptr;
-    int st = get_plan(kKindSumsq, 0, 0, md, s, &p);
+    int st = get_plan(kKindSumsq, wbf16, 0, md, s, &p);
     if (st != FLORA_OK) return st;
-    FLORA_HIP(launch_weight_sumsq(p->cur_mats, count, static_cast<float*>(p->d_work), s));
+    FLORA_HIP(launch_weight_sumsq(p->cur_mats, count, wbf16, static_cast<float*>(p->d_work), s));
     return FLORA_OK;
 }
 
@@ -850,7 +850,6 @@ static int check_update(const flora_matrix_t* mats, int count, int r, flora_dtyp
         if (ada && mats[l].weight_sumsq && (reinterpret_cast<uintptr_t>(mats[l].weight_sumsq) & 3u))
             return FLORA_ERR_INVALID;
     }
-    if (weight_dtype != FLORA_F32) return FLORA_ERR_UNSUPPORTED;
     return FLORA_OK;
 }
 
@@ -926,7 +925,7 @@ int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = update_chunk(mats + c0, cn, r, u, false, static_cast<hipStream_t>(hip_stream));
+        st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, false, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;
@@ -950,15 +949,15 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
         }
         st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, next, s);
         if (st != FLORA_OK) return st;
-        st = update_chunk(mats + c0, cn, r, u, next, s);
+        st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, next, s);
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;
 }
 
-int flora_weight_sumsq(const flora_matrix_t* mats, int count, void* hip_stream)
+int flora_weight_sumsq(const flora_matrix_t* mats, int count, flora_dtype_t weight_dtype, void* hip_stream)
 {
-    if (count < 0 || (count > 0 && !mats)) return FLORA_ERR_INVALID;
+    if (count < 0 || (count > 0 && !mats) || !dtype_ok((int)weight_dtype)) return FLORA_ERR_INVALID;
     for (int l = 0; l < count; ++l) {
         if (mats[l].n < 1 || mats[l].m < 1) return FLORA_ERR_INVALID;
         if (mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24)) return FLORA_ERR_INVALID;
@@ -968,7 +967,7 @@ int flora_weight_sumsq(const flora_matrix_t* mats, int count, void* hip_stream)
     }
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
-        const int st = sumsq_chunk(mats + c0, cn, static_cast<hipStream_t>(hip_stream));
+        const int st = sumsq_chunk(mats + c0, cn, weight_dtype == FLORA_BF16, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
     v4f stage[F4];
     fetch(stage, it.row0);
     TilePre<MODE> pre_cur, pre_nxt;
-    epilogue_fetch<MODE>(pre_cur, M, it.row0, row_end, j, jok);
+    epilogue_fetch<MODE, OT>(pre_cur, M, it.row0, row_end, j, jok);
     stash(stage, 0);
     __syncthreads();
 
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
         const bool more = rb + 32 < row_end;
         if (more) {
             fetch(stage, rb + 32);
-            epilogue_fetch<MODE>(pre_nxt, M, rb + 32, row_end, j, jok);
+            epilogue_fetch<MODE, OT>(pre_nxt, M, rb + 32, row_end, j, jok);
         }
 
         f32x16 acc;
@@ -275,7 +275,25 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         rows = rows < 0 ? 0 : (rows > 32 ? 32 : rows);
         const long long base = rb < n ? rb : 0;
         if (MODE == kModeOut) return make_rsrc(reinterpret_cast<OT*>(M.out) + base * m, rows * m * (long long)sizeof(OT));
-        return make_rsrc(M.weight + base * m, rows * m * 4);
+        return make_rsrc(reinterpret_cast<OT*>(M.weight) + base * m, rows * m * (long long)sizeof(OT));
+    };
+    // four consecutive elements of W (fp32: 16 bytes, bf16: 8 bytes per lane); the store returns
+    // the values as stored
+    auto load_w4 = [&](rsrc_t rw, uint32_t off) -> v4f {
+        if (sizeof(OT) == 4) return buf_load_f4(rw, off);
+        const v2u pk = buf_load_u2(rw, off);
+        return v4f{bf16_bits_to_f32(pk.x & 0xffffu), bf16_bits_to_f32(pk.x >> 16),
+                   bf16_bits_to_f32(pk.y & 0xffffu), bf16_bits_to_f32(pk.y >> 16)};
+    };
+    auto store_w4 = [&](rsrc_t rw, uint32_t off, v4f v) -> v4f {
+        if (sizeof(OT) == 4) {
+            buf_store_f4(rw, off, v);
+            return v;
+        }
+        const v2u pk = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+        buf_store_u2(rw, off, pk);
+        return v4f{bf16_bits_to_f32(pk.x & 0xffffu), bf16_bits_to_f32(pk.x >> 16),
+                   bf16_bits_to_f32(pk.y & 0xffffu), bf16_bits_to_f32(pk.y >> 16)};
     };
     auto vrsrc = [&](long long rb) -> rsrc_t {
         long long rows = row_end - rb;
@@ -286,16 +304,19 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     auto woff = [&](int pp) -> uint32_t {
         return cok ? ((uint32_t)(er + 8 * pp) * (uint32_t)m + c0) * (uint32_t)sizeof(OT) : kOob;
     };
+    auto voff = [&](int pp) -> uint32_t {     // the second moment is always fp32
+        return cok ? ((uint32_t)(er + 8 * pp) * (uint32_t)m + c0) * 4u : kOob;
+    };
     auto pre_fetch = [&](VecPre<MODE>& pre, long long rb) {
         if (kUsesW) {
             const rsrc_t rw = wrsrc(rb);
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp) pre.w[pp] = buf_load_f4(rw, woff(pp));
+            for (int pp = 0; pp < 4; ++pp) pre.w[pp] = load_w4(rw, woff(pp));
         }
         if (kUsesV) {
             const rsrc_t rv = vrsrc(rb);
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp) pre.v[pp] = buf_load_f4(rv, woff(pp));
+            for (int pp = 0; pp < 4; ++pp) pre.v[pp] = buf_load_f4(rv, voff(pp));
         }
         if (MODE == kModeFactored) {
 #pragma unroll
@@ -375,8 +396,8 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
 #pragma unroll
             for (int pp = 0; pp < 4; ++pp) {
                 const v4f a4 = gt[pp], w = pre0.w[pp];
-                buf_store_f4(rw, woff(pp), v4f{w.x - p.coef * a4.x, w.y - p.coef * a4.y,
-                                               w.z - p.coef * a4.z, w.w - p.coef * a4.w});
+                store_w4(rw, woff(pp), v4f{w.x - p.coef * a4.x, w.y - p.coef * a4.y,
+                                           w.z - p.coef * a4.z, w.w - p.coef * a4.w});
             }
         } else if (MODE == kModeFactored) {
             const rsrc_t rw = wrsrc(rb);
@@ -384,9 +405,8 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
             for (int pp = 0; pp < 4; ++pp) {
                 const float ri = rsqrtf(pre0.rs[pp]);
                 const v4f a4 = gt[pp], w = pre0.w[pp];
-                const v4f wn = {w.x - kfac[0] * ri * a4.x, w.y - kfac[1] * ri * a4.y,
-                                w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w};
-                buf_store_f4(rw, woff(pp), wn);
+                const v4f wn = store_w4(rw, woff(pp), v4f{w.x - kfac[0] * ri * a4.x, w.y - kfac[1] * ri * a4.y,
+                                                          w.z - kfac[2] * ri * a4.z, w.w - kfac[3] * ri * a4.w});
                 // sum of the new W^2 (rows past the end and columns past m contribute exact zeros:
                 // their old weights read as zero and their factors are zero)
                 total = __builtin_fmaf(wn.x, wn.x, total);
@@ -407,7 +427,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 const v4f g2 = {a2 * a4.x * a4.x, a2 * a4.y * a4.y, a2 * a4.z * a4.z, a2 * a4.w * a4.w};
                 const v4f vn = {p.beta2 * v.x + omb * (g2.x + p.eps1), p.beta2 * v.y + omb * (g2.y + p.eps1),
                                 p.beta2 * v.z + omb * (g2.z + p.eps1), p.beta2 * v.w + omb * (g2.w + p.eps1)};
-                buf_store_f4(rv, woff(pp), vn);
+                buf_store_f4(rv, voff(pp), vn);
                 const float u2 = ((g2.x / vn.x + g2.y / vn.y) + (g2.z / vn.z + g2.w / vn.w));
                 total += ok ? u2 : 0.f;
             }
@@ -417,9 +437,8 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
             for (int pp = 0; pp < 4; ++pp) {
                 const bool ok = cok && (rb + er + 8 * pp < row_end);
                 const v4f a4 = gt[pp], w = pre0.w[pp], v = pre0.v[pp];
-                const v4f wn = {w.x - kfull * rsqrtf(v.x) * a4.x, w.y - kfull * rsqrtf(v.y) * a4.y,
-                                w.z - kfull * rsqrtf(v.z) * a4.z, w.w - kfull * rsqrtf(v.w) * a4.w};
-                buf_store_f4(rw, woff(pp), wn);
+                const v4f wn = store_w4(rw, woff(pp), v4f{w.x - kfull * rsqrtf(v.x) * a4.x, w.y - kfull * rsqrtf(v.y) * a4.y,
+                                                          w.z - kfull * rsqrtf(v.z) * a4.z, w.w - kfull * rsqrtf(v.w) * a4.w});
                 const float w2 = ((wn.x * wn.x + wn.y * wn.y) + (wn.z * wn.z + wn.w * wn.w));
                 total += ok ? w2 : 0.f;
             }
@@ -513,7 +532,7 @@ hipError_t launch_mode_vec(const MatDev* mats, const WorkItem* items, int nitems
         hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeSgd:
-        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeSgd, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeStats:
         hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
@@ -522,13 +541,13 @@ hipError_t launch_mode_vec(const MatDev* mats, const WorkItem* items, int nitems
         hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFactored:
-        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFactored, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull1:
         hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull2:
-        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_vec_kernel<R, kModeFull2, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;
@@ -546,7 +565,7 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
         hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeSgd:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeSgd, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeStats:
         hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
@@ -555,13 +574,13 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
         hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFactored:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFactored, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull1:
         hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull2:
-        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_bf16_kernel<R, kModeFull2, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;
@@ -573,11 +592,13 @@ template <int R>
 hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int mode,
                     int out_is_bf16, int vec, DecompressParams p, hipStream_t s)
 {
+    // modes that read or write the n x m array whose element type the caller chose (out, or W)
+    const bool typed = mode == kModeOut || mode == kModeSgd || mode == kModeFactored || mode == kModeFull2;
     if (vec) {
-        if (mode == kModeOut && out_is_bf16) return launch_mode_vec<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+        if (typed && out_is_bf16) return launch_mode_vec<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
         return launch_mode_vec<R, float>(mats, items, nitems, seeds, mode, p, s);
     }
-    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+    if (typed && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
     return launch_mode<R, float>(mats, items, nitems, seeds, mode, p, s);
 }
 

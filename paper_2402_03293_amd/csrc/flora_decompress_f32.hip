@@ -68,12 +68,12 @@ __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __res
     v4f a_cur[H / 4], a_nxt[H / 4];
     TilePre<MODE> pre_cur, pre_nxt;
     load_state(a_cur, it.row0);
-    epilogue_fetch<MODE>(pre_cur, M, it.row0, row_end, j, jok);
+    epilogue_fetch<MODE, OT>(pre_cur, M, it.row0, row_end, j, jok);
     for (long long rb = it.row0; rb < row_end; rb += 32) {
         const bool more = rb + 32 < row_end;
         if (more) {
             load_state(a_nxt, rb + 32);
-            epilogue_fetch<MODE>(pre_nxt, M, rb + 32, row_end, j, jok);
+            epilogue_fetch<MODE, OT>(pre_nxt, M, rb + 32, row_end, j, jok);
         }
         f32x16 acc;
 #pragma unroll
@@ -102,7 +102,7 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
         hipLaunchKernelGGL((decompress_f32_kernel<R, kModeOut, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeSgd:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeSgd, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeSgd, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeStats:
         hipLaunchKernelGGL((decompress_f32_kernel<R, kModeStats, float>), grid, block, 0, s, mats, items, seeds, p);
@@ -111,13 +111,13 @@ hipError_t launch_mode(const MatDev* mats, const WorkItem* items, int nitems, co
         hipLaunchKernelGGL((decompress_f32_kernel<R, kModeRms, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFactored:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFactored, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFactored, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull1:
         hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFull1, float>), grid, block, 0, s, mats, items, seeds, p);
         break;
     case kModeFull2:
-        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFull2, float>), grid, block, 0, s, mats, items, seeds, p);
+        hipLaunchKernelGGL((decompress_f32_kernel<R, kModeFull2, OT>), grid, block, 0, s, mats, items, seeds, p);
         break;
     default:
         return hipErrorInvalidValue;
@@ -129,7 +129,9 @@ template <int R>
 hipError_t launch_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int mode,
                     int out_is_bf16, DecompressParams p, hipStream_t s)
 {
-    if (mode == kModeOut && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
+    // modes that read or write the n x m array whose element type the caller chose (out, or W)
+    const bool typed = mode == kModeOut || mode == kModeSgd || mode == kModeFactored || mode == kModeFull2;
+    if (typed && out_is_bf16) return launch_mode<R, uint16_t>(mats, items, nitems, seeds, mode, p, s);
     return launch_mode<R, float>(mats, items, nitems, seeds, mode, p, s);
 }
 

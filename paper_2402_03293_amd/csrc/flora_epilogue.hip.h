@@ -65,7 +65,7 @@ __device__ __forceinline__ int tile_row(int v, int g) { return 8 * (v / 4) + 4 *
 
 // Addresses inside a tile are a workgroup-uniform base (first row of the tile) plus a 32-bit
 // per-lane element offset row * m + column: 33 m < 2^32 is guaranteed by the host (m <= 2^26).
-template <int MODE>
+template <int MODE, typename OT>
 __device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev& M, long long rb,
                                                long long row_end, long long j, bool jok)
 {
@@ -76,11 +76,11 @@ __device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev&
     const uint32_t jc = jok ? (uint32_t)j : m32 - 1u;
     const int last = (int)(row_end - 1 - rb);          // last valid row of the tile, relative
     if (MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2) {
-        const float* tb = M.weight + rb * M.m;
+        const OT* tb = reinterpret_cast<const OT*>(M.weight) + rb * M.m;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
-            pre.w[v] = ldg(tb + (rr * m32 + jc));
+            pre.w[v] = load_elem(tb + (rr * m32 + jc));
         }
     }
     if (MODE == kModeFull1 || MODE == kModeFull2) {
@@ -127,11 +127,11 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
             }
         }
     } else if (MODE == kModeSgd) {
-        float* wb = M.weight + rb * m;
+        OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             if (jok && tile_row(v, g) < rows_here)
-                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - p.coef * acc[v]);
+                store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - p.coef * acc[v]);
     } else if (MODE == kModeStats) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -145,13 +145,13 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
         for (int v = 0; v < 16; ++v)
             if (jok && tile_row(v, g) < rows_here) e.colsum += acc[v] * acc[v] * e.kfac / pre.rs[v];
     } else if (MODE == kModeFactored) {
-        float* wb = M.weight + rb * m;
+        OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             if (jok && tile_row(v, g) < rows_here) {
-                const float wn = pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v];
-                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), wn);
-                e.colsum = __builtin_fmaf(wn, wn, e.colsum);
+                const float wn = store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
+                                            pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v]);
+                e.colsum = __builtin_fmaf(wn, wn, e.colsum);     // of the value as stored
             }
     } else if (MODE == kModeFull1) {
         float* vb = M.vfull + rb * m;
@@ -164,12 +164,12 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
                 e.colsum += gt * gt / vn;
             }
     } else if (MODE == kModeFull2) {
-        float* wb = M.weight + rb * m;
+        OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             if (jok && tile_row(v, g) < rows_here) {
-                const float wn = pre.w[v] - e.kfac * rsqrtf(pre.v[v]) * acc[v];
-                stg(wb + ((uint32_t)tile_row(v, g) * m32 + j32), wn);
+                const float wn = store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
+                                            pre.w[v] - e.kfac * rsqrtf(pre.v[v]) * acc[v]);
                 e.colsum = __builtin_fmaf(wn, wn, e.colsum);
             }
     }

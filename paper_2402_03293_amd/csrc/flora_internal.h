@@ -8,7 +8,7 @@ namespace flora {
 // Device-side image of one weight matrix (built on the host from flora_matrix_t).
 struct MatDev {
     const void* grad;
-    float* weight;
+    void* weight;       // n x m, fp32 or bf16
     float* state;
     float* row_stat;
     float* col_stat;
@@ -151,6 +151,17 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
 {
     return __builtin_bit_cast(float, b << 16);
 }
+// One element of an n x m array of fp32 or bf16 (weights, decompressed gradients): loads give the
+// value as fp32, stores round to nearest even and return the value that was stored.
+__device__ __forceinline__ float load_elem(const float* p) { return *(const FLORA_GLOBAL float*)p; }
+__device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_bits_to_f32(*(const FLORA_GLOBAL uint16_t*)p); }
+__device__ __forceinline__ float store_elem(float* p, float v) { *(FLORA_GLOBAL float*)p = v; return v; }
+__device__ __forceinline__ float store_elem(uint16_t* p, float v)
+{
+    const uint32_t b = f32_to_bf16_bits(v);
+    *(FLORA_GLOBAL uint16_t*)p = (uint16_t)b;
+    return bf16_bits_to_f32(b);
+}
 
 // ---- launchers implemented in the kernel translation units ----------------
 hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out, uint32_t* raw_out,
@@ -173,7 +184,7 @@ hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, flo
 hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
                                hipStream_t s);
 hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s);
-hipError_t launch_weight_sumsq(const MatDev* mats, int count, float* partials, hipStream_t s);
+hipError_t launch_weight_sumsq(const MatDev* mats, int count, int weight_is_bf16, float* partials, hipStream_t s);
 hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s);
 
 // Tiling constants the host needs to build work tables.

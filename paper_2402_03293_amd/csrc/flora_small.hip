@@ -99,23 +99,32 @@ __global__ __launch_bounds__(256) void wsumsq_finalize_kernel(const MatDev* __re
 
 // Sum of W^2 from scratch: workgroup b of matrix l sums the float4s b, b + 256, ... of W
 // (and the last n m % 4 values in workgroup 0) into partials[l][b].
+template <typename WT>
 __global__ __launch_bounds__(256) void weight_sumsq_kernel(const MatDev* __restrict__ mats,
                                                            float* __restrict__ partials)
 {
     __shared__ float lds[256];
     const MatDev& M = mats[blockIdx.y];
     const long long total = M.n * M.m, total4 = total >> 2;
+    const WT* W = reinterpret_cast<const WT*>(M.weight);
     const int tid = threadIdx.x;
     float s = 0.f;
     for (long long i = (long long)blockIdx.x * 256 + tid; i < total4; i += (long long)kSumsqBlocks * 256) {
-        const v4f w = ldg4(M.weight + 4 * i);
+        v4f w;
+        if (sizeof(WT) == 4) {
+            w = ldg4(reinterpret_cast<const float*>(W) + 4 * i);
+        } else {
+            const v2u pk = ldg2(reinterpret_cast<const uint16_t*>(W) + 4 * i);
+            w = v4f{bf16_bits_to_f32(pk.x & 0xffffu), bf16_bits_to_f32(pk.x >> 16),
+                    bf16_bits_to_f32(pk.y & 0xffffu), bf16_bits_to_f32(pk.y >> 16)};
+        }
         s = __builtin_fmaf(w.x, w.x, s);
         s = __builtin_fmaf(w.y, w.y, s);
         s = __builtin_fmaf(w.z, w.z, s);
         s = __builtin_fmaf(w.w, w.w, s);
     }
     if (blockIdx.x == 0 && tid < (int)(total & 3)) {
-        const float w = ldg(M.weight + 4 * total4 + tid);
+        const float w = load_elem(W + 4 * total4 + tid);
         s = __builtin_fmaf(w, w, s);
     }
     const float tot = block_sum_256(s, lds);
@@ -165,11 +174,14 @@ hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_weight_sumsq(const MatDev* mats, int count, float* partials, hipStream_t s)
+hipError_t launch_weight_sumsq(const MatDev* mats, int count, int weight_is_bf16, float* partials, hipStream_t s)
 {
     if (count == 0) return hipSuccess;
     static_assert(kSumsqBlocks == 256, "one partial per thread of the finalize kernel");
-    hipLaunchKernelGGL(weight_sumsq_kernel, dim3(kSumsqBlocks, (unsigned)count), dim3(256), 0, s, mats, partials);
+    if (weight_is_bf16)
+        hipLaunchKernelGGL(weight_sumsq_kernel<uint16_t>, dim3(kSumsqBlocks, (unsigned)count), dim3(256), 0, s, mats, partials);
+    else
+        hipLaunchKernelGGL(weight_sumsq_kernel<float>, dim3(kSumsqBlocks, (unsigned)count), dim3(256), 0, s, mats, partials);
     hipLaunchKernelGGL(weight_sumsq_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, partials);
     return hipGetLastError();
 }

@@ -92,7 +92,7 @@ def lib():
         L.flora_apply_update.restype = ci
         L.flora_fused_step.argtypes = [MP, ci, ci, ci, ci, cf, cf, ci, ctypes.POINTER(Update), vp]
         L.flora_fused_step.restype = ci
-        L.flora_weight_sumsq.argtypes = [MP, ci, vp]
+        L.flora_weight_sumsq.argtypes = [MP, ci, ci, vp]
         L.flora_weight_sumsq.restype = ci
         L.flora_adafactor_schedule.argtypes = [ctypes.c_uint64, ctypes.POINTER(cf), ctypes.POINTER(cf)]
         L.flora_adafactor_schedule.restype = None
@@ -274,8 +274,8 @@ def unfactored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d
                   int(scale_parameter), eps2)
 
 
-def weight_sumsq(mats, stream=None):
-    _check(lib().flora_weight_sumsq(mats, len(mats), _stream(stream)), "flora_weight_sumsq")
+def weight_sumsq(mats, weight_dtype: int = F32, stream=None):
+    _check(lib().flora_weight_sumsq(mats, len(mats), weight_dtype, _stream(stream)), "flora_weight_sumsq")
 
 
 def adafactor_schedule(t: int):

@@ -17,8 +17,8 @@ Schedules follow the paper's two algorithms:
   into the momentum, b = (1 - beta) / tau, which by linearity is Algorithm 2 on the mean
   gradient of the cycle.
 
-Only 2-D fp32 parameters are accepted (the paper projects the attention and feed-forward weight
-matrices).  Gradients may be fp32 or bf16 at every rank; at ranks 64/128/256 bf16 gradients take
+Only 2-D parameters, fp32 or bf16, are accepted (the paper projects the attention and feed-forward
+weight matrices).  Gradients may be fp32 or bf16 at every rank; at ranks 64/128/256 bf16 gradients take
 the fastest kernel (``param.grad_dtype = torch.bfloat16`` makes autograd produce them).
 """
 from __future__ import annotations
@@ -47,8 +47,11 @@ class Flora:
         if tau < 1 or kappa < 1 or not (0.0 <= beta < 1.0):
             raise ValueError("tau >= 1, kappa >= 1, 0 <= beta < 1")
         for p in self.params:
-            if p.dim() != 2 or p.dtype != torch.float32 or not p.is_cuda or not p.is_contiguous():
-                raise ValueError("parameters must be contiguous 2-D fp32 CUDA tensors")
+            if p.dim() != 2 or p.dtype not in (torch.float32, torch.bfloat16) or not p.is_cuda or not p.is_contiguous():
+                raise ValueError("parameters must be contiguous 2-D fp32 or bf16 CUDA tensors")
+        if len({p.dtype for p in self.params}) != 1:
+            raise ValueError("all parameters must have one dtype")
+        self.wdt = flora.F32 if self.params[0].dtype == torch.float32 else flora.BF16
         self.r, self.lr, self.tau, self.beta, self.kappa, self.rule = r, lr, tau, beta, kappa, rule
         self.global_seed = seed
         self.eps1, self.eps2, self.clip_d = eps1, eps2, clip_d
@@ -122,7 +125,7 @@ class Flora:
         if any(self.params[l].grad is None for l in idx):
             raise RuntimeError("a parameter has no gradient")
         if self.sumsq is not None and self.scale_parameter and not self._sumsq_ready:
-            flora.weight_sumsq(self._descriptors(list(range(len(self.params)))), stream)
+            flora.weight_sumsq(self._descriptors(list(range(len(self.params)))), self.wdt, stream)
             self._sumsq_ready = True
         gdt = self._grad_dtype(idx)
         momentum = self.beta > 0.0
@@ -149,7 +152,7 @@ class Flora:
             a = b = 1.0
         if last:
             upd = self._update_struct(t + 1, 1.0 if momentum else 1.0 / self.tau, zero_after=not momentum)
-            flora.fused_step(mats, self.r, gdt, flora.F32, a, b, transfer, upd, stream)
+            flora.fused_step(mats, self.r, gdt, self.wdt, a, b, transfer, upd, stream)
         else:
             if transfer:
                 flora.momentum_transfer(mats, self.r, stream)

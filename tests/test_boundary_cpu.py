@@ -88,7 +88,7 @@ def test_update_validation():
     ok = _mats()
     sgd = flora.sgd_update(0.1)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, None, None) == flora.ERR_INVALID
-    assert L.flora_apply_update(ok, 1, 16, flora.BF16, ctypes.byref(sgd), None) == flora.ERR_UNSUPPORTED
+    assert L.flora_apply_update(ok, 1, 16, 2, ctypes.byref(sgd), None) == flora.ERR_INVALID       # no such dtype
     assert L.flora_apply_update(ok, 1, 16, 5, ctypes.byref(sgd), None) == flora.ERR_INVALID
     bad_rule = flora.Update(9, 0.1, 1.0, 0, 0, 0, 0, 0, 0)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(bad_rule), None) == flora.ERR_INVALID
@@ -99,8 +99,7 @@ def test_update_validation():
         == flora.ERR_INVALID
     now = flora.matrices([(16, 16)], states=[0x3000], seeds=[1])
     assert L.flora_apply_update(now, 1, 16, flora.F32, ctypes.byref(sgd), None) == flora.ERR_INVALID
-    assert L.flora_fused_step(ok, 1, 64, flora.F32, flora.BF16, 0.9, 0.1, 0, ctypes.byref(sgd), None) \
-        == flora.ERR_UNSUPPORTED            # bf16 weights
+    assert L.flora_fused_step(ok, 1, 64, flora.F32, 3, 0.9, 0.1, 0, ctypes.byref(sgd), None) == flora.ERR_INVALID
     assert L.flora_fused_step(ok, 0, 64, flora.BF16, flora.F32, 0.9, 0.1, 0, ctypes.byref(sgd), None) == flora.OK
 
 
@@ -148,9 +147,10 @@ def test_adafactor_rules_validation_and_schedule_helper():
     assert L.flora_apply_update(alias, 1, 16, flora.F32, C.byref(unf), None) == flora.ERR_INVALID
     odd = flora.matrices([(16, 16)], second_moments=[0x5004], **base)
     assert L.flora_apply_update(odd, 1, 16, flora.F32, C.byref(unf), None) == flora.ERR_INVALID
-    assert L.flora_weight_sumsq(no_v, 1, None) == flora.ERR_INVALID
-    assert L.flora_weight_sumsq(None, 1, None) == flora.ERR_INVALID
-    assert L.flora_weight_sumsq(no_v, 0, None) == flora.OK
+    assert L.flora_weight_sumsq(no_v, 1, flora.F32, None) == flora.ERR_INVALID
+    assert L.flora_weight_sumsq(None, 1, flora.F32, None) == flora.ERR_INVALID
+    assert L.flora_weight_sumsq(no_v, 0, flora.F32, None) == flora.OK
+    assert L.flora_weight_sumsq(no_v, 0, 5, None) == flora.ERR_INVALID
     # published schedules: rho_t = min(1e-2, 1/sqrt(t)), beta2_t = 1 - t^-0.8
     assert flora.adafactor_schedule(1) == (pytest.approx(1e-2, rel=1e-6), 0.0)
     assert flora.adafactor_schedule(32)[1] == pytest.approx(0.9375, rel=1e-6)

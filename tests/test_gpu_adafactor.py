@@ -266,7 +266,76 @@ def test_adafactor_argument_errors_launch_nothing():
     assert status(with_v, flora.unfactored_update(0.1, 1.0, 1.5, 1e-30, 1.0)) == flora.ERR_INVALID
     alias = flora.matrices([(n, m)], weights=[W], states=[S], seeds=[1], second_moments=[W])
     assert status(alias, flora.unfactored_update(0.1, 1.0, 0.0, 1e-30, 1.0)) == flora.ERR_INVALID
-    assert lib.flora_weight_sumsq(with_v, 1, None) == flora.ERR_INVALID      # no weight_sumsq pointer
+    assert lib.flora_weight_sumsq(with_v, 1, flora.F32, None) == flora.ERR_INVALID      # no weight_sumsq pointer
     sync()
     assert torch.equal(W, W0)
     assert float(V.abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------ bf16 weights
+def bf16_round(x):
+    """fp64 -> nearest bf16 (ties to even), through fp32 as the kernels do."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16 << 16
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("n,m,r", [(130, 200, 16), (77, 70, 8), (300, 520, 64), (257, 264, 256), (100, 131, 128)])
+@pytest.mark.parametrize("rule", ["sgd", "factored", "unfactored"])
+def test_updates_on_bf16_weights(n, m, r, rule):
+    # the update is computed in fp32 from the bf16 weights and rounded when stored: against the
+    # oracle's result rounded the same way the stored weights may differ by one bf16 step where
+    # the exact value falls next to a rounding boundary, and nowhere by more
+    seed = 9500 + r
+    S = rand((n, r), seed)
+    W0 = rand((n, m), seed + 1, scale=0.5).to(torch.bfloat16).contiguous()
+    W = W0.clone()
+    ss = torch.zeros(4, device=DEV)
+    kw = dict(weights=[W], states=[S], seeds=[seed], weight_sumsqs=[ss])
+    lr, alpha = 0.05, 0.5
+    Gt = oracle.decompress(to64(S), m, seed, alpha=alpha)
+    W064 = to64(W0)
+    if rule == "sgd":
+        mats = flora.matrices([(n, m)], **kw)
+        flora.apply_update(mats, r, flora.BF16, flora.sgd_update(lr, alpha))
+        Wr = oracle.sgd(W064, Gt, lr)
+    elif rule == "factored":
+        R, K = torch.zeros(n, device=DEV), torch.zeros(m, device=DEV)
+        mats = flora.matrices([(n, m)], row_stats=[R], col_stats=[K], **kw)
+        flora.weight_sumsq(mats, flora.BF16)
+        flora.apply_update(mats, r, flora.BF16, flora.factored_update(lr, alpha, 0.0, 1e-30, 1.0, scale_parameter=True))
+        Wr, _, _ = oracle.adafactor_step(W064, Gt, R=np.zeros(n), K=np.zeros(m), beta2=0.0, step=lr)
+    else:
+        V0 = (rand((n, m), seed + 2).abs() + 0.1).contiguous()
+        V = V0.clone()
+        mats = flora.matrices([(n, m)], second_moments=[V], **kw)
+        flora.weight_sumsq(mats, flora.BF16)
+        flora.apply_update(mats, r, flora.BF16, flora.unfactored_update(lr, alpha, 0.8, 1e-30, 1.0, scale_parameter=True))
+        Wr, Vr = oracle.adafactor_step(W064, Gt, V=to64(V0), beta2=0.8, step=lr)
+        assert rel_fro(to64(V), Vr) < 2 * tol_for(r)
+    sync()
+    assert W.dtype == torch.bfloat16
+    got, want = to64(W), bf16_round(Wr)
+    dg, do = got - W064, Wr - W064
+    # one bf16 step at that magnitude, plus what the path's own error can move a value
+    step = np.maximum(np.abs(want), np.abs(got)) * 2.0 ** -7 + tol_for(r) * np.abs(do).max()
+    assert (np.abs(got - want) <= step).all()
+    # the movement itself, where it is well above the rounding of the weights
+    big = np.abs(do) > 8 * np.abs(W064) * 2.0 ** -8
+    if big.sum() > 100:
+        assert rel_fro(dg[big], do[big]) < 0.1
+    mismatches = (got != want).mean()
+    assert mismatches < (0.002 if r <= 32 else 0.08), mismatches
+    if rule != "sgd":
+        assert float(ss[0]) == pytest.approx(float((got ** 2).sum()), rel=5e-6)   # of the stored values
+
+
+def test_weight_sumsq_bf16_and_vector_kernel_tails():
+    shapes = [(3, 5), (64, 64), (257, 1023), (33, 4)]
+    Ws = [rand(s, 200 + i).to(torch.bfloat16).contiguous() for i, s in enumerate(shapes)]
+    out = torch.zeros((len(shapes), 4), device=DEV)
+    mats = flora.matrices(shapes, weights=Ws, weight_sumsqs=[out[i] for i in range(len(shapes))])
+    flora.weight_sumsq(mats, flora.BF16)
+    sync()
+    for i, W in enumerate(Ws):
+        assert float(out[i, 0]) == pytest.approx(float((to64(W) ** 2).sum()), rel=2e-6)

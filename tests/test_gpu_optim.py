@@ -149,9 +149,12 @@ def test_front_end_rejects_what_the_library_cannot_take():
     p1 = torch.nn.Parameter(torch.zeros(8, device=DEV))
     with pytest.raises(ValueError):
         optim.Flora([p1], 16, 0.1)
-    p2 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV, dtype=torch.bfloat16))
+    p2 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV, dtype=torch.float16))
     with pytest.raises(ValueError):
         optim.Flora([p2], 16, 0.1)
+    with pytest.raises(ValueError):                             # one dtype for all parameters
+        optim.Flora([torch.nn.Parameter(torch.zeros((8, 8), device=DEV)),
+                     torch.nn.Parameter(torch.zeros((8, 8), device=DEV, dtype=torch.bfloat16))], 16, 0.1)
     with pytest.raises(ValueError):
         optim.Flora([torch.nn.Parameter(torch.zeros((8, 8), device=DEV))], 16, None, rule="sgd")
     p3 = torch.nn.Parameter(torch.zeros((8, 8), device=DEV))
@@ -159,3 +162,26 @@ def test_front_end_rejects_what_the_library_cannot_take():
     p3.grad = torch.zeros((8, 8), device=DEV)
     with pytest.raises(flora.FloraError):
         opt.step()
+
+
+def test_bf16_parameters_layer_by_layer():
+    # bf16 weights and bf16 gradients, momentum, r = 64: the stored weights follow the oracle's
+    # trajectory to within the rounding of bf16 weights (a relative 2^-8 per stored value)
+    r, beta, kappa, lr, steps, gseed = 64, 0.9, 3, 0.05, 5, 21
+    g = torch.Generator(device="cpu").manual_seed(1)
+    params = [torch.nn.Parameter((0.1 * torch.randn(*s, generator=g)).to(torch.bfloat16).to(DEV)) for s in SHAPES]
+    W = [to64(p) for p in params]
+    grads = make_grads(steps, 2, True)
+    opt = optim.Flora(params, r, lr, beta=beta, kappa=kappa, rule="sgd", seed=gseed)
+    opt.attach()
+    for t in range(steps):
+        loss = sum((p.float() * gg).sum() for p, gg in zip(params, grads[t]))
+        loss.backward()
+    torch.cuda.synchronize()
+    ref = oracle.Algorithm2(SHAPES, r, beta, kappa, gseed)
+    for t in range(steps):
+        _, W = ref.step([to64(gg) for gg in grads[t]], W, lr=lr)
+    for l in range(len(SHAPES)):
+        assert params[l].dtype == torch.bfloat16
+        assert rel_fro(to64(opt.state[l]), ref.M[l]) < 2e-2
+        assert rel_fro(to64(params[l]), W[l]) < 2e-2
