@@ -3,8 +3,8 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input:
   * Algorithm-1 workloads (1, 2, 4): one accumulation cycle = tau grouped compress
-    launches over tau distinct gradient sets, then decompress + update (+ state reset),
-    then a new seed per matrix.
+    launches over tau distinct gradient sets (the first one overwrites the accumulator,
+    which is the cycle's reset), then decompress + update, then a new seed per matrix.
   * Algorithm-2 workloads (3, 5): one optimizer step = (transfer when t = 0 mod kappa)
     + EMA compress + decompress + SGD update.
 The default workload is configuration 2 of the benchmark spec (T5-small shapes, fp32, r = 16,
@@ -169,7 +169,7 @@ def main():
             v["seed_next"][:] = cur if nxt is None else nxt
 
     alpha_u = 1.0 / wl.tau if wl.algorithm == 1 else 1.0
-    zero_after = wl.algorithm == 1
+    zero_after = False      # Algorithm 1's reset is the a = 0 of the next cycle's first compress
 
     if args.momentum:
         alpha_u, zero_after = 1.0, False     # the momentum is not reset and its decompression carries no 1/tau
@@ -185,10 +185,9 @@ def main():
         upd = adafactor_update(1)
     elif wl.rule == "factored":
         ex = wl.extra
-        upd = flora.factored_update(wl.lr, 1.0 / wl.tau, ex["beta2"], ex["eps1"], ex["clip_d"],
-                                    zero_state_after=True)
+        upd = flora.factored_update(wl.lr, 1.0 / wl.tau, ex["beta2"], ex["eps1"], ex["clip_d"])
     elif wl.algorithm == 1:
-        upd = flora.sgd_update(wl.lr, 1.0 / wl.tau, zero_state_after=True)
+        upd = flora.sgd_update(wl.lr, 1.0 / wl.tau)
     else:
         upd = flora.sgd_update(wl.lr, 1.0)
 
@@ -234,14 +233,13 @@ def main():
                     timed("compress", lambda: flora.compress(mt, r, gdt, a_, b_, stream))
                 else:
                     mt = mats_sets[g]
-                    timed("compress", lambda: flora.compress(mt, r, gdt, 1.0, 1.0, stream))
+                    a0_ = 0.0 if i == 0 else 1.0
+                    timed("compress", lambda: flora.compress(mt, r, gdt, a0_, 1.0, stream))
             if args.momentum == "folded":
                 for v in views:
                     v["seed_next"][:] = mom_seeds
                 mt = mats_sets[0]
                 timed("transfer", lambda: flora.transfer_accumulate(mt, r, beta, (1.0 - beta) / wl.tau, mom, stream))
-                for st_ in states:
-                    st_.zero_()
             mt = mats_mom[0]
             u_ = upd if rule in ("adafactor", "unfactored") else upd_mom
             timed("update", lambda: flora.apply_update(mt, r, flora.F32, u_, stream))
@@ -249,10 +247,12 @@ def main():
             seeds = flora.derive_seeds(gseed, 0, count, epoch)
             set_seeds(seeds)
         elif wl.algorithm == 1:
-            for _ in range(wl.tau):
+            for i in range(wl.tau):
                 mt = mats_sets[tstate["gi"] % nsets]
                 tstate["gi"] += 1
-                timed("compress", lambda: flora.compress(mt, r, gdt, 1.0, 1.0, stream))
+                # the cycle's accumulator starts at zero: the first micro-batch overwrites it (a = 0)
+                a_ = 0.0 if i == 0 else 1.0
+                timed("compress", lambda: flora.compress(mt, r, gdt, a_, 1.0, stream))
             mt = mats_sets[0]
             timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
             epoch += 1

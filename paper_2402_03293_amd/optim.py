@@ -149,9 +149,11 @@ class Flora:
             a = self.beta if first else 1.0
             b = (1.0 - self.beta) / self.tau
         else:
-            a = b = 1.0
+            # Algorithm 1: the accumulator starts each cycle at zero, so the cycle's first
+            # micro-batch overwrites it
+            a, b = (0.0 if first else 1.0), 1.0
         if last:
-            upd = self._update_struct(t + 1, 1.0 if momentum else 1.0 / self.tau, zero_after=not momentum)
+            upd = self._update_struct(t + 1, 1.0 if momentum else 1.0 / self.tau, zero_after=False)
             flora.fused_step(mats, self.r, gdt, self.wdt, a, b, transfer, upd, stream)
         else:
             if transfer:

@@ -110,7 +110,6 @@ def test_accumulation_cycles(rule, layerwise):
             W, _, _ = oracle.algorithm1_cycle(W, gsteps, r, gseed, c, 0.0, rule="adafactor", factored=fac)
     for l in range(len(SHAPES)):
         assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < 1e-4
-        assert float(opt.state[l].abs().max()) == 0.0          # reset at the end of the cycle
         assert opt.updates[l] == cycles and opt.epoch[l] == cycles
 
 
