@@ -578,3 +578,21 @@ def test_accumulating_straight_into_the_momentum_is_algorithm2_on_the_mean_gradi
         M = oracle.compress(G, r, seed, state=M, a=beta if i == 0 else 1.0, b=(1.0 - beta) / tau)
     want = oracle.compress(sum(grads) / tau, r, seed, state=M0, a=beta, b=1.0 - beta)
     np.testing.assert_allclose(M, want, rtol=1e-12, atol=1e-14)
+
+
+def test_projection_entries_match_the_stored_fixture():
+    # regression pin of the generator as a whole (the fixture is written by
+    # tests/golden/make_golden.py from the oracle alone)
+    rows = [l for l in open(os.path.join(GOLDEN, "projection_entries.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for line in rows:
+        head, vals = line.split(":")
+        seed, row, r = (int(x) for x in head.split())
+        want = [float.fromhex(v) for v in vals.split()]
+        got = [oracle.A_elem(seed, row, k, r) for k in range(8)]
+        # (to a few ulps: the host's libm may pick another code path for log / sin / cos)
+        assert got == pytest.approx(want, rel=1e-14, abs=0)
+        # and the same numbers through the matrix route for rows that fit
+        if row < 20000:
+            A = oracle.materialise_A(seed, row + 1, r)
+            assert list(A[row, :8]) == got
