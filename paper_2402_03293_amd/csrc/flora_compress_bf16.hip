@@ -279,8 +279,9 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         uint32_t pk[NQ / 2][4];
 #pragma unroll
         for (int e = 0; e < NQ; e += 2) {
-            Quad z0, z1;
-            normal_quad_pair(seed_lo, seed_hi, j + e, q0 + gen_q, cgen, z0, z1);
+            const Quad z0 = normal_quad(seed_lo, seed_hi, j + e, q0 + gen_q, cgen);
+            __builtin_amdgcn_sched_barrier(0);
+            const Quad z1 = normal_quad(seed_lo, seed_hi, j + e + 1, q0 + gen_q, cgen);
 #pragma unroll
             for (int i = 0; i < 4; ++i) pk[e / 2][i] = pack_bf16x2(z0.z[i], z1.z[i]);
             __builtin_amdgcn_sched_barrier(0);

@@ -96,37 +96,6 @@ __device__ __forceinline__ Quad normal_quad(uint32_t seed_lo, uint32_t seed_hi, 
     return o;
 }
 
-// Two quads at once, (j, q) and (j + 1, q), with the rounds of the two Philox chains written
-// side by side: one chain alone is a sequence of dependent multiplies and xors whose latencies a
-// wave with few neighbours on its SIMD cannot hide.
-__device__ __forceinline__ void normal_quad_pair(uint32_t seed_lo, uint32_t seed_hi, uint64_t j, uint32_t q,
-                                                 float neg2_ln2_over_r, Quad& za, Quad& zb)
-{
-    uint32_t a0 = (uint32_t)j, a1 = q, a2 = (uint32_t)(j >> 32), a3 = kDomainA;
-    uint32_t b0 = (uint32_t)(j + 1), b1 = q, b2 = (uint32_t)((j + 1) >> 32), b3 = kDomainA;
-    uint32_t k0 = seed_lo, k1 = seed_hi;
-#pragma unroll
-    for (int round = 0; round < 10; ++round) {
-        const uint64_t pa0 = (uint64_t)kPhiloxM0 * (uint64_t)a0;
-        const uint64_t pb0 = (uint64_t)kPhiloxM0 * (uint64_t)b0;
-        const uint64_t pa1 = (uint64_t)kPhiloxM1 * (uint64_t)a2;
-        const uint64_t pb1 = (uint64_t)kPhiloxM1 * (uint64_t)b2;
-        const uint32_t na0 = (uint32_t)(pa1 >> 32) ^ a1 ^ k0;
-        const uint32_t nb0 = (uint32_t)(pb1 >> 32) ^ b1 ^ k0;
-        const uint32_t na2 = (uint32_t)(pa0 >> 32) ^ a3 ^ k1;
-        const uint32_t nb2 = (uint32_t)(pb0 >> 32) ^ b3 ^ k1;
-        a1 = (uint32_t)pa1; b1 = (uint32_t)pb1;
-        a3 = (uint32_t)pa0; b3 = (uint32_t)pb0;
-        a0 = na0; b0 = nb0; a2 = na2; b2 = nb2;
-        k0 += kPhiloxW0;
-        k1 += kPhiloxW1;
-    }
-    box_muller(a0, a1, neg2_ln2_over_r, za.z[0], za.z[1]);
-    box_muller(b0, b1, neg2_ln2_over_r, zb.z[0], zb.z[1]);
-    box_muller(a2, a3, neg2_ln2_over_r, za.z[2], za.z[3]);
-    box_muller(b2, b3, neg2_ln2_over_r, zb.z[2], zb.z[3]);
-}
-
 __host__ __device__ __forceinline__ float neg2_ln2_over(int r)
 {
     return -1.3862943611198906f / (float)r;
