@@ -24,7 +24,7 @@ namespace {
 
 constexpr int kBK = 64;         // columns of G per tile
 constexpr int kLda = kBK + 4;   // padded LDS row (floats)
-constexpr int kPF = 4;          // G tiles in flight per wave (register stages)
+constexpr int kPF = 2;          // G tiles in flight per wave (register stages)
 
 __device__ __forceinline__ v4f load4(const float* rowp, long long col, long long m, bool fast)
 {
@@ -163,6 +163,23 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // A workgroup that owns its rows outright fetches the old state now, so that the read is
+    // long finished when the epilogue needs it (clamped addresses; unused lanes read row n-1).
+    float old[MT][NT][4];
+    const bool direct = it.nparts <= 1;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int k = (nt * 16 + li < R) ? nt * 16 + li : R - 1;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                long long row = (long long)it.row0 + wave * (MT * 16) + mt * 16 + 4 * g + v;
+                if (row > n - 1) row = n - 1;
+                old[mt][nt][v] = (direct && kg == 0 && a != 0.f) ? ldg(state + row * R + k) : 0.f;
+            }
+        }
 
     auto mfma_tile = [&](const v4f (&gt)[MT][4], int buf) {
 #pragma unroll
@@ -318,20 +335,6 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         return;
     }
 
-    // All old values are fetched first (clamped addresses), then the new ones are stored.
-    float old[MT][NT][4];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int k = (nt * 16 + li < R) ? nt * 16 + li : R - 1;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                long long row = (long long)it.row0 + wave * (MT * 16) + mt * 16 + 4 * g + v;
-                if (row > n - 1) row = n - 1;
-                old[mt][nt][v] = (a != 0.f) ? ldg(state + row * R + k) : 0.f;
-            }
-        }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
