@@ -53,6 +53,9 @@ def parse_args():
                          "(beta 0.9) and update from that.  folded: accumulate into C under one projection, "
                          "then M <- beta M + ((1-beta)/tau) C A_c^T A_m (flora_transfer_accumulate); direct: one "
                          "projection for both, every micro-batch is compressed straight into M")
+    ap.add_argument("--input-map", default=None, choices=["square"],
+                    help="compress the elementwise square of the gradients (flora_compress_mapped: the compressed "
+                         "EMA of the second moment) instead of the gradients; same launches otherwise")
     ap.add_argument("--layerwise", type=int, default=0, metavar="K",
                     help="Algorithm-2 workloads only: one flora_fused_step call per K consecutive matrices (the "
                          "layer-by-layer invocation of an update-in-backward training loop; K = 4 is one "
@@ -217,6 +220,12 @@ def main():
 
     tstate = {"t": 0, "gi": 0, "u": 0}
 
+    def do_compress(mt, a_, b_):
+        if args.input_map == "square":
+            flora.compress_mapped(mt, r, gdt, flora.INPUT_SQUARE, a_, b_, stream)
+        else:
+            flora.compress(mt, r, gdt, a_, b_, stream)
+
     def one_step():
         nonlocal seeds, epoch, upd
         if rule in ("adafactor", "unfactored"):
@@ -230,11 +239,11 @@ def main():
                 if args.momentum == "direct":
                     mt = mats_mom[g]
                     a_, b_ = (beta if i == 0 else 1.0), (1.0 - beta) / wl.tau
-                    timed("compress", lambda: flora.compress(mt, r, gdt, a_, b_, stream))
+                    timed("compress", lambda: do_compress(mt, a_, b_))
                 else:
                     mt = mats_sets[g]
                     a0_ = 0.0 if i == 0 else 1.0
-                    timed("compress", lambda: flora.compress(mt, r, gdt, a0_, 1.0, stream))
+                    timed("compress", lambda: do_compress(mt, a0_, 1.0))
             if args.momentum == "folded":
                 for v in views:
                     v["seed_next"][:] = mom_seeds
@@ -252,7 +261,7 @@ def main():
                 tstate["gi"] += 1
                 # the cycle's accumulator starts at zero: the first micro-batch overwrites it (a = 0)
                 a_ = 0.0 if i == 0 else 1.0
-                timed("compress", lambda: flora.compress(mt, r, gdt, a_, 1.0, stream))
+                timed("compress", lambda: do_compress(mt, a_, 1.0))
             mt = mats_sets[0]
             timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
             epoch += 1
@@ -281,7 +290,7 @@ def main():
                 return
             mt = mats_sets[tstate["gi"] % nsets]
             tstate["gi"] += 1
-            timed("compress", lambda: flora.compress(mt, r, gdt, wl.beta, 1.0 - wl.beta, stream))
+            timed("compress", lambda: do_compress(mt, wl.beta, 1.0 - wl.beta))
             timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
             tstate["t"] += 1
 
@@ -363,7 +372,7 @@ def main():
                    "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
                    "beta": wl.beta if wl.algorithm == 2 else None,
                    "kappa": wl.kappa if wl.algorithm == 2 else None,
-                   "rule": rule, "momentum_from_accumulator": args.momentum, "layerwise": args.layerwise, "grad_sets_in_ring": nsets,
+                   "rule": rule, "momentum_from_accumulator": args.momentum, "input_map": args.input_map, "layerwise": args.layerwise, "grad_sets_in_ring": nsets,
                    "grad_bytes_per_step": grad_bytes_step},
         "roofline": roofline,
         "kernels": kern,

@@ -119,6 +119,22 @@ typedef struct flora_update {
 int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
                    float a, float b, void* hip_stream);
 
+/* An elementwise map applied to `grad` on its way into the compression. */
+typedef enum { FLORA_INPUT_IDENTITY = 0, FLORA_INPUT_SQUARE = 1 } flora_input_map_t;
+
+/* The compressed EMA of another statistic (closing remark of Section 2.3: the scheme of
+ * Algorithm 2 extends to other EMA-based statistics):
+ *     state <- a * state + b * (phi(grad) A(seed)),   phi elementwise
+ * FLORA_INPUT_IDENTITY is flora_compress; FLORA_INPUT_SQUARE makes `state` the compressed
+ * second moment (a = beta2, b = 1 - beta2), squared in registers so that grad^2 is never
+ * written anywhere.  flora_decompress of such a state is an unbiased estimate of the statistic
+ * (not a non-negative one), and flora_momentum_transfer moves it to a new projection like any
+ * other state.  At ranks <= 32 the square is taken in fp32; at ranks >= 64 it is squared in
+ * fp32 and rounded to bf16 for the matrix cores.  Arguments, requirements and errors as for
+ * flora_compress; an unknown map is FLORA_ERR_INVALID. */
+int flora_compress_mapped(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                          flora_input_map_t map, float a, float b, void* hip_stream);
+
 /* Decompression (Algorithm 1, decompression line, with the printed 1/n read
  * as 1/tau; Algorithm 2, yield):
  *     out[l] <- alpha * state A(seed)^T        (n x m, row-major, out_dtype)
@@ -194,7 +210,7 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
  * this set of shapes.  kind 0: flora_compress, 1: flora_decompress and the update passes,
  * 2: the state <- state T pass of the transfer, 3: its T = A^T A' pass (ranks 64 and above; a
  * workgroup takes columns [first column, end column) of chunk `part` and slab `rank slice` of
- * the rows of T).  Returns the number of workgroups (or a
+ * the rows of T), 4: flora_compress_mapped with a map other than the identity.  Returns the number of workgroups (or a
  * negative flora_status_t) and writes up to `cap` of them to `out`, 12 int64 each:
  * matrix, first row, rows, first column, rank slice (compress) or column chunk (decompress),
  * row-block index, end column, part, number of parts, arrival counter, offset of the partial

@@ -158,6 +158,19 @@ def compress(G, r: int, seed: int, state=None, a: float = 1.0, b: float = 1.0,
     return st
 
 
+def compress_mapped(G, r: int, seed: int, input_map: str, state=None, a: float = 1.0, b: float = 1.0) -> np.ndarray:
+    """Compressed EMA of another statistic (closing remark of Section 2.3): the compression line with
+    phi(G) in place of G, phi elementwise; "square" gives the second moment's term G * G."""
+    G = _f64c(G)
+    if input_map == "identity":
+        X = G
+    elif input_map == "square":
+        X = G * G
+    else:
+        raise ValueError(input_map)
+    return compress(X, r, seed, state=state, a=a, b=b)
+
+
 def decompress(state, m: int, seed: int, alpha: float = 1.0, regen: bool = False) -> np.ndarray:
     st = _f64c(state)
     n, r = st.shape

@@ -72,7 +72,8 @@ struct Plan {
     int count = 0;
     int r = 0;
     int variant = 0;          // compress: 0 fp32 grads, 1 bf16 grads on the fp32 path, 2 bf16 path,
-                              // 3 bf16 path with fp32 grads (rounded in registers)
+                              // 3 bf16 path with fp32 grads (rounded in registers); + 4 when the
+                              // input is mapped (squared) on the way in
     uint64_t shape_hash = 0;
     std::vector<MatDev> host_mats;      // shapes and tiling fields (pointers unset)
     std::vector<WorkItem> items;        // main work table
@@ -189,7 +190,7 @@ void build_compress_bf16_items(Plan& p)
     // bytes of extra traffic per block, so parts stay at 768 columns or more.
     // Unaligned sets take the narrow kernel with the largest rows-per-workgroup (128 * mt)
     // that still gives the chip two workgroups per compute unit.
-    bool aligned = p.variant != 3;      // fp32 gradients take the narrow kernel
+    bool aligned = (p.variant & 3) == 2;      // fp32 gradients take the narrow kernel
     for (int l = 0; l < p.count; ++l)   // 16-byte aligned rows, 32-bit byte offsets within 64 rows
         aligned = aligned && (p.host_mats[l].m % 8) == 0 && p.host_mats[l].m <= (1LL << 23);
     const int wide_slice = (p.r == 64) ? 64 : 128;
@@ -457,7 +458,7 @@ int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
         M.n = n; M.m = m;
     }
     if (kind == kKindCompress) {
-        if (p->variant >= 2) build_compress_bf16_items(*p);
+        if ((p->variant & 3) >= 2) build_compress_bf16_items(*p);
         else build_compress_f32_items(*p);
     } else if (kind == kKindTransfer) {
         build_transfer_T_items(*p);
@@ -656,7 +657,7 @@ static void fill_seed_args(SeedArgs& sa, const flora_matrix_t* mats, int count, 
 }
 
 // ---- one chunk (count <= kMaxSeedArgs) of each entry point; arguments already validated ----
-static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype, int map,
                           float a, float b, bool use_next, hipStream_t s)
 {
     std::vector<MatDev> md((size_t)count);
@@ -669,7 +670,7 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     fill_seed_args(sa, mats, count, use_next);
     const int variant = rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : (grad_dtype == FLORA_BF16 ? 1 : 0);
     Plan* p = nullptr;
-    int st = get_plan(kKindCompress, variant, r, md, s, &p);
+    int st = get_plan(kKindCompress, variant + 4 * map, r, md, s, &p);
     if (st != FLORA_OK) return st;
     const MatDev* dm = p->cur_mats;
     const WorkItem* di = p->d_items;
@@ -678,8 +679,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
         uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
                                                                    round_up(p->ws_floats * 4, 256))
                                        : nullptr;
-        FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, variant == 3, a, b, partials,
-                                          counters, s));
+        FLORA_HIP(launch_compress_bf16_mt(dm, di, (int)p->items.size(), sa, r, p->mt, variant == 3, map, a, b,
+                                          partials, counters, s));
     }
     else {
         // column groups per workgroup: two for whole rows; one when the pieces are 512 columns
@@ -688,8 +689,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
         uint32_t* counters = p->d_work ? reinterpret_cast<uint32_t*>(static_cast<char*>(p->d_work) +
                                                                    round_up(p->ws_floats * 4, 256))
                                        : nullptr;
-        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, a, b, kg, p->mt, partials,
-                                      counters, s));
+        FLORA_HIP(launch_compress_f32(dm, di, (int)p->items.size(), sa, r, variant == 1, map, a, b, kg, p->mt,
+                                      partials, counters, s));
     }
     return FLORA_OK;
 }
@@ -867,7 +868,23 @@ int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t g
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, false, static_cast<hipStream_t>(hip_stream));
+        st = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, false, static_cast<hipStream_t>(hip_stream));
+        if (st != FLORA_OK) return st;
+    }
+    return FLORA_OK;
+}
+
+int flora_compress_mapped(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
+                          flora_input_map_t map, float a, float b, void* hip_stream)
+{
+    if ((int)map != FLORA_INPUT_IDENTITY && (int)map != FLORA_INPUT_SQUARE) return FLORA_ERR_INVALID;
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    st = check_grads(mats, count, r, grad_dtype);
+    if (st != FLORA_OK) return st;
+    std::lock_guard<std::mutex> guard(g_lock);
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        st = compress_chunk(mats + c0, cn, r, grad_dtype, (int)map, a, b, false, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
     }
     return FLORA_OK;
@@ -947,7 +964,7 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
             st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s);
             if (st != FLORA_OK) return st;
         }
-        st = compress_chunk(mats + c0, cn, r, grad_dtype, a, b, next, s);
+        st = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, next, s);
         if (st != FLORA_OK) return st;
         st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, next, s);
         if (st != FLORA_OK) return st;
@@ -992,7 +1009,7 @@ int flora_debug_generate(uint64_t seed, int64_t m, int r, float* A_out, uint32_t
 int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, int r,
                                flora_dtype_t grad_dtype, int64_t* out, int64_t cap, int64_t* info)
 {
-    if (count < 0 || (count > 0 && !mats) || kind < 0 || kind > 3) return FLORA_ERR_INVALID;
+    if (count < 0 || (count > 0 && !mats) || kind < 0 || kind > 4) return FLORA_ERR_INVALID;
     if (!rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
     for (int l = 0; l < count; ++l)
         if (mats[l].n < 1 || mats[l].m < 1 || mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24))
@@ -1002,10 +1019,11 @@ int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, 
     p.count = count; p.r = r;
     p.host_mats.resize((size_t)count);
     for (int l = 0; l < count; ++l) { p.host_mats[(size_t)l].n = mats[l].n; p.host_mats[(size_t)l].m = mats[l].m; }
-    if (kind == 0) {
+    if (kind == 0 || kind == 4) {
         p.kind = kKindCompress;
         p.variant = rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : (grad_dtype == FLORA_BF16 ? 1 : 0);
-        if (p.variant >= 2) build_compress_bf16_items(p);
+        if (kind == 4) p.variant += 4;
+        if ((p.variant & 3) >= 2) build_compress_bf16_items(p);
         else build_compress_f32_items(p);
     } else {
         p.kind = kind == 1 ? kKindDecompress : kKindTransfer;
@@ -1126,6 +1144,6 @@ void flora_shutdown(void)
     g_plans.clear();
 }
 
-int flora_version(void) { return 200; }
+int flora_version(void) { return 300; }
 
 }  // extern "C"

@@ -3,7 +3,9 @@
 // (Algorithm 1, compression line; Algorithm 2, EMA line).  A is rounded to
 // bf16 as it is generated; products are exact in fp32 and accumulated in fp32
 // (v_mfma_f32_32x32x16_bf16).  G is bf16, or fp32 rounded to bf16 (nearest even)
-// in registers on its way to the matrix cores (first kernel below only).
+// in registers on its way to the matrix cores (first kernel below only).  Both
+// kernels also take the elementwise square of G as their input (MAP = 1: squared in
+// fp32, then rounded to bf16), for the compressed EMA of the second moment.
 //
 // The cost that matters here is regenerating A, not the contraction: every
 // workgroup that sweeps the m columns of G must rebuild all the A rows it
@@ -28,7 +30,14 @@ constexpr int kBK = 32;            // columns of G per tile
 constexpr int kLda = kBK + 8;      // padded LDS row (bf16 elements): 80 bytes
 constexpr int kRS = kCompressBf16Slice;
 
-template <int MT, typename GT>
+// both halves of a packed pair of bf16 squared in fp32 and rounded back
+__device__ __forceinline__ uint32_t square_bf16x2(uint32_t w)
+{
+    const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xffff0000u);
+    return pack_bf16x2(lo * lo, hi * hi);
+}
+
+template <int MT, typename GT, int MAP>
 __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __restrict__ mats,
                                                             const WorkItem* __restrict__ items,
                                                             const SeedArgs seeds, int R, float a, float b)
@@ -61,11 +70,16 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
         rowp[mt] = G + row * m;
     }
 
-    // element c of the row as bf16 bits (zero past the end)
+    // element c of the row (mapped) as bf16 bits (zero past the end)
     auto elem = [&](const GT* rp, long long c) -> uint32_t {
         if (c >= m) return 0u;
-        if constexpr (kF32) return f32_to_bf16_bits(ldg(reinterpret_cast<const float*>(rp) + c));
-        else return ldg(reinterpret_cast<const uint16_t*>(rp) + c);
+        if constexpr (kF32) {
+            const float x = ldg(reinterpret_cast<const float*>(rp) + c);
+            return f32_to_bf16_bits(MAP == 1 ? x * x : x);
+        } else {
+            const uint32_t w = ldg(reinterpret_cast<const uint16_t*>(rp) + c);
+            return MAP == 1 ? (square_bf16x2(w) & 0xffffu) : w;
+        }
     };
 
     auto load_tile = [&](v4u (&dst)[MT][2], int tile) {
@@ -75,7 +89,8 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
             for (int mt = 0; mt < MT; ++mt) {
                 if constexpr (kF32) {
                     const float* rp = reinterpret_cast<const float*>(rowp[mt]) + j0;
-                    const v4f f0 = ldg4(rp), f1 = ldg4(rp + 4), f2 = ldg4(rp + 8), f3 = ldg4(rp + 12);
+                    v4f f0 = ldg4(rp), f1 = ldg4(rp + 4), f2 = ldg4(rp + 8), f3 = ldg4(rp + 12);
+                    if (MAP == 1) { f0 = f0 * f0; f1 = f1 * f1; f2 = f2 * f2; f3 = f3 * f3; }
                     dst[mt][0] = v4u{pack_bf16x2(f0.x, f0.y), pack_bf16x2(f0.z, f0.w),
                                      pack_bf16x2(f1.x, f1.y), pack_bf16x2(f1.z, f1.w)};
                     dst[mt][1] = v4u{pack_bf16x2(f2.x, f2.y), pack_bf16x2(f2.z, f2.w),
@@ -84,6 +99,12 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
                     const uint16_t* rp = reinterpret_cast<const uint16_t*>(rowp[mt]) + j0;
                     dst[mt][0] = ldg4(rp);
                     dst[mt][1] = ldg4(rp + 8);
+                    if (MAP == 1) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+                            dst[mt][h] = v4u{square_bf16x2(dst[mt][h].x), square_bf16x2(dst[mt][h].y),
+                                             square_bf16x2(dst[mt][h].z), square_bf16x2(dst[mt][h].w)};
+                    }
                 }
             }
         } else {
@@ -208,7 +229,7 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 constexpr int kWBK = 64;             // columns of G per tile
 constexpr int kWLda = kWBK + 8;      // padded LDS row (bf16 elements): 144 bytes
 
-template <int CT, int RT>   // per wave: CT 16-wide column tiles (RS = 16 CT), RT 16-row tiles
+template <int CT, int RT, int MAP>   // per wave: CT 16-wide column tiles (RS = 16 CT), RT 16-row tiles; MAP 1: input squared
 __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* __restrict__ mats,
                                                                  const WorkItem* __restrict__ items,
                                                                  const SeedArgs seeds, int R, float a, float b,
@@ -308,6 +329,12 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     auto mfma_tile = [&](v4u (&gt)[RT][2], int buf, int tile) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
+            if (MAP == 1) {      // the statistic's term: G squared in fp32, rounded back to bf16
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    gt[rt][s] = v4u{square_bf16x2(gt[rt][s].x), square_bf16x2(gt[rt][s].y),
+                                    square_bf16x2(gt[rt][s].z), square_bf16x2(gt[rt][s].w)};
+            }
             bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsA[buf][li][32 * s + 8 * g]);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
@@ -470,44 +497,65 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
 
 }  // namespace
 
+namespace {
+
+template <int MAP>
+hipError_t launch_wide(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int r, int mt,
+                       float a, float b, float* partials, uint32_t* counters, hipStream_t s)
+{
+    const dim3 grid((unsigned)nitems), block(512);
+    if (mt == 8) {
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+    } else {
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 2, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+    }
+    return hipGetLastError();
+}
+
+template <int MAP>
+hipError_t launch_narrow(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int r, int mt,
+                         int grad_is_f32, float a, float b, dim3 grid, dim3 block, hipStream_t s)
+{
+    (void)nitems;
+    switch (mt) {
+    case 1:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<1, float, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<1, uint16_t, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
+    case 2:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<2, float, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<2, uint16_t, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
+    case 4:
+        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<4, float, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        else hipLaunchKernelGGL((compress_bf16_kernel<4, uint16_t, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b);
+        break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
 // All items of one launch share one MT (rows per workgroup = 128 * MT; 8 and 16 select the wide
 // kernel), chosen by the host.  partials / counters: workspace of the wide kernel's shared-column
 // mode (may be null when no item has nparts > 1).
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
-                                   const SeedArgs& seeds, int r, int mt, int grad_is_f32, float a, float b,
+                                   const SeedArgs& seeds, int r, int mt, int grad_is_f32, int map, float a, float b,
                                    float* partials, uint32_t* counters, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
     if (grad_is_f32 && mt > 4) return hipErrorInvalidValue;   // fp32 gradients: first kernel only
-    if (mt == 8 || mt == 16) {   // wide kernel: 512 (8) or 256 (16) rows per workgroup, rank slices of 128 (64 at r = 64)
-        const dim3 grid((unsigned)nitems), block(512);
-        if (mt == 8) {
-            if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-            else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-        } else {
-            if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 2>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-            else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-        }
-        return hipGetLastError();
-    }
+    if (map != 0 && map != 1) return hipErrorInvalidValue;
+    if (mt == 8 || mt == 16)     // wide kernel: 512 (8) or 256 (16) rows per workgroup, rank slices of 128 (64 at r = 64)
+        return (map == 1) ? launch_wide<1>(mats, items, nitems, seeds, r, mt, a, b, partials, counters, s)
+                          : launch_wide<0>(mats, items, nitems, seeds, r, mt, a, b, partials, counters, s);
     const dim3 grid((unsigned)nitems), block(256);
-    switch (mt) {
-    case 1:
-        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<1, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        else hipLaunchKernelGGL((compress_bf16_kernel<1, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        break;
-    case 2:
-        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<2, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        else hipLaunchKernelGGL((compress_bf16_kernel<2, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        break;
-    case 4:
-        if (grad_is_f32) hipLaunchKernelGGL((compress_bf16_kernel<4, float>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        else hipLaunchKernelGGL((compress_bf16_kernel<4, uint16_t>), grid, block, 0, s, mats, items, seeds, r, a, b);
-        break;
-    default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    return (map == 1) ? launch_narrow<1>(mats, items, nitems, seeds, r, mt, grad_is_f32, a, b, grid, block, s)
+                      : launch_narrow<0>(mats, items, nitems, seeds, r, mt, grad_is_f32, a, b, grid, block, s);
 }
 
 }  // namespace flora

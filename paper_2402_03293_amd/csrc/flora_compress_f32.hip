@@ -2,7 +2,9 @@
 //     state <- a * state + b * (G A(seed))
 // (Algorithm 1, compression line with a = b = 1; Algorithm 2, EMA line with
 // a = beta, b = 1 - beta).  G is fp32 or bf16 and is used exactly; products and
-// sums are fp32 (v_mfma_f32_16x16x4_f32).
+// sums are fp32 (v_mfma_f32_16x16x4_f32).  With MAP = 1 the input is the elementwise
+// square of G, taken in fp32 on the operand registers (the compressed EMA of another
+// statistic that Section 2.3 closes with: here the second moment).
 //
 // One workgroup owns 64 * MT rows of one matrix and sweeps all m columns in
 // tiles of 64.  Its 4 * KG waves form KG column groups of 4 waves; group kg
@@ -53,7 +55,7 @@ __device__ __forceinline__ v4f load4(const uint16_t* rowp, long long col, long l
     return v;
 }
 
-template <int R, typename GT, int MT, int KG>
+template <int R, typename GT, int MT, int KG, int MAP>
 __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __restrict__ mats,
                                                                 const WorkItem* __restrict__ items,
                                                                 const SeedArgs seeds, float a, float b,
@@ -193,9 +195,11 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(gt[mt][c][t], bv[nt][t],
+                    for (int t = 0; t < 4; ++t) {
+                        const float x = gt[mt][c][t];
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(MAP == 1 ? x * x : x, bv[nt][t],
                                                                            acc[mt][nt], 0, 0, 0);
+                    }
         }
     };
 
@@ -348,44 +352,49 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         }
 }
 
-template <int R, typename GT, int MT>
+template <int R, typename GT, int MT, int MAP>
 hipError_t launch_mt(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                      float a, float b, int kgroups, float* partials, uint32_t* counters, hipStream_t s)
 {
     const dim3 grid((unsigned)nitems);
     switch (kgroups) {
-    case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1>), grid, dim3(256), 0, s, mats, items, seeds, a, b, partials, counters); break;
-    case 2: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 2>), grid, dim3(512), 0, s, mats, items, seeds, a, b, partials, counters); break;
-    case 4: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 4>), grid, dim3(1024), 0, s, mats, items, seeds, a, b, partials, counters); break;
+    case 1: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 1, MAP>), grid, dim3(256), 0, s, mats, items, seeds, a, b, partials, counters); break;
+    case 2: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 2, MAP>), grid, dim3(512), 0, s, mats, items, seeds, a, b, partials, counters); break;
+    case 4: hipLaunchKernelGGL((compress_f32_kernel<R, GT, MT, 4, MAP>), grid, dim3(1024), 0, s, mats, items, seeds, a, b, partials, counters); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 template <int R, typename GT>
-hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
+hipError_t launch_one(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int map,
                       float a, float b, int kgroups, int mt, float* partials, uint32_t* counters, hipStream_t s)
 {
-    if (mt == 1) return launch_mt<R, GT, 1>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
-    if (mt == 2) return launch_mt<R, GT, 2>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+    if (map == 0) {
+        if (mt == 1) return launch_mt<R, GT, 1, 0>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+        if (mt == 2) return launch_mt<R, GT, 2, 0>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+    } else if (map == 1) {
+        if (mt == 1) return launch_mt<R, GT, 1, 1>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+        if (mt == 2) return launch_mt<R, GT, 2, 1>(mats, items, nitems, seeds, a, b, kgroups, partials, counters, s);
+    }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, float* partials,
-                               uint32_t* counters, hipStream_t s)
+                               int r, int grad_is_bf16, int map, float a, float b, int kgroups, int mt,
+                               float* partials, uint32_t* counters, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     if (!grad_is_bf16) {
-        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
-        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
-        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 8) return launch_one<8, float>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
+        if (r == 16) return launch_one<16, float>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
+        if (r == 32) return launch_one<32, float>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
     } else {
-        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
-        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
-        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, a, b, kgroups, mt, partials, counters, s);
+        if (r == 8) return launch_one<8, uint16_t>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
+        if (r == 16) return launch_one<16, uint16_t>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
+        if (r == 32) return launch_one<32, uint16_t>(mats, items, nitems, seeds, map, a, b, kgroups, mt, partials, counters, s);
     }
     return hipErrorInvalidValue;
 }

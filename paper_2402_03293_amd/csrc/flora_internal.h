@@ -168,10 +168,10 @@ hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out
                                  hipStream_t s);
 hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s);
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
-                               int r, int grad_is_bf16, float a, float b, int kgroups, int mt, float* partials,
-                               uint32_t* counters, hipStream_t s);
+                               int r, int grad_is_bf16, int map, float a, float b, int kgroups, int mt,
+                               float* partials, uint32_t* counters, hipStream_t s);
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
-                                   const SeedArgs& seeds, int r, int mt, int grad_is_f32, float a, float b,
+                                   const SeedArgs& seeds, int r, int mt, int grad_is_f32, int map, float a, float b,
                                    float* partials, uint32_t* counters, hipStream_t s);
 hipError_t launch_decompress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                  int r, int mode, int out_is_bf16, DecompressParams p, hipStream_t s);

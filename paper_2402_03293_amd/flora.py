@@ -20,6 +20,8 @@ ERR_DEVICE = -3
 RULE_SGD = 0
 RULE_FACTORED = 1
 RULE_UNFACTORED = 2
+INPUT_IDENTITY = 0
+INPUT_SQUARE = 1
 
 _LIB_PATH = Path(__file__).resolve().parent / "libflora.so"
 
@@ -82,6 +84,8 @@ def lib():
         vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
         L.flora_compress.argtypes = [MP, ci, ci, ci, cf, cf, vp]
         L.flora_compress.restype = ci
+        L.flora_compress_mapped.argtypes = [MP, ci, ci, ci, ci, cf, cf, vp]
+        L.flora_compress_mapped.restype = ci
         L.flora_decompress.argtypes = [MP, ci, ci, cf, ctypes.POINTER(vp), ci, vp]
         L.flora_decompress.restype = ci
         L.flora_momentum_transfer.argtypes = [MP, ci, ci, vp]
@@ -123,7 +127,7 @@ def lib():
 
 
 EXPORTS = [
-    "flora_compress", "flora_decompress", "flora_momentum_transfer", "flora_transfer_accumulate",
+    "flora_compress", "flora_compress_mapped", "flora_decompress", "flora_momentum_transfer", "flora_transfer_accumulate",
     "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
     "flora_debug_work_items", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
@@ -175,6 +179,11 @@ def _stream(stream) -> Optional[int]:
 
 def compress(mats, r: int, grad_dtype: int, a: float = 1.0, b: float = 1.0, stream=None):
     _check(lib().flora_compress(mats, len(mats), r, grad_dtype, a, b, _stream(stream)), "flora_compress")
+
+
+def compress_mapped(mats, r: int, grad_dtype: int, input_map: int, a: float = 1.0, b: float = 1.0, stream=None):
+    _check(lib().flora_compress_mapped(mats, len(mats), r, grad_dtype, input_map, a, b, _stream(stream)),
+           "flora_compress_mapped")
 
 
 def decompress(mats, r: int, alpha: float, outs, out_dtype: int, stream=None):

@@ -57,6 +57,10 @@ def test_compress_validation():
     assert L.flora_compress(ok, 1, 12, flora.F32, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(ok, 1, 512, flora.BF16, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(ok, 1, 16, 7, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress_mapped(ok, 1, 16, flora.F32, 2, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress_mapped(ok, 1, 16, flora.F32, -1, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress_mapped(None, 1, 16, flora.F32, flora.INPUT_SQUARE, 1.0, 1.0, None) == flora.ERR_INVALID
+    assert L.flora_compress_mapped(ok, 1, 12, flora.F32, flora.INPUT_SQUARE, 1.0, 1.0, None) == flora.ERR_UNSUPPORTED
     assert L.flora_compress(_mats(n=0), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(_mats(m=-3), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
     assert L.flora_compress(_mats(grad=0x1004), 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID

@@ -225,6 +225,60 @@ def test_compress_bf16_shared_columns(r, kc, mt):
         assert rel_fro(to64(states[l]), ref) < 6e-3
 
 
+# compressed EMA of the second moment: the square is taken in registers on the way in.  Every
+# rank, both gradient types, ragged shapes and unaligned rows, forced launch shapes, two steps of
+# the EMA; then the state decompresses to what the oracle's state decompresses to.
+@pytest.mark.parametrize("gdt", ["f32", "bf16"])
+@pytest.mark.parametrize("n,m,r,mt", [(70, 200, 8, 0), (130, 1001, 16, 2), (257, 520, 32, 0), (300, 520, 64, 0),
+                                      (257, 1001, 128, 2), (700, 264, 256, 4), (513, 31, 64, 1),
+                                      (700, 264, 256, 8), (1100, 520, 128, 16), (530, 1160, 64, 8)])
+def test_compress_mapped_square(n, m, r, mt, gdt):
+    dt = torch.float32 if gdt == "f32" else torch.bfloat16
+    fd = flora.F32 if gdt == "f32" else flora.BF16
+    seed, beta2 = 4100 + n + m + r, 0.9
+    G1, G2 = rand((n, m), seed, dt), rand((n, m), seed + 1, dt, scale=3.0)
+    st = torch.zeros((n, r), device=DEV)
+    knob = "compress_f32_mt" if r <= 32 else "compress_bf16_mt"
+    flora.set_tuning(knob, mt)
+    try:
+        flora.compress_mapped(flora.matrices([(n, m)], grads=[G1], states=[st], seeds=[seed]), r, fd,
+                              flora.INPUT_SQUARE, 0.0, 1.0 - beta2)
+        flora.compress_mapped(flora.matrices([(n, m)], grads=[G2], states=[st], seeds=[seed]), r, fd,
+                              flora.INPUT_SQUARE, beta2, 1.0 - beta2)
+        ident = torch.zeros((n, r), device=DEV)
+        flora.compress_mapped(flora.matrices([(n, m)], grads=[G1], states=[ident], seeds=[seed]), r, fd,
+                              flora.INPUT_IDENTITY, 0.0, 1.0)
+        plain = torch.zeros((n, r), device=DEV)
+        flora.compress(flora.matrices([(n, m)], grads=[G1], states=[plain], seeds=[seed]), r, fd, 0.0, 1.0)
+        sync()
+    finally:
+        flora.set_tuning(knob, 0)
+    ref = oracle.compress_mapped(to64(G1), r, seed, "square", a=0.0, b=1.0 - beta2)
+    ref = oracle.compress_mapped(to64(G2), r, seed, "square", state=ref, a=beta2, b=1.0 - beta2)
+    e = rel_fro(to64(st), ref)
+    assert e < (TOL_F32 if r <= 32 else 6e-3), e
+    rows = np.linalg.norm(to64(st) - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert rows.max() < tol_for(r), (int(rows.argmax()), float(rows.max()))
+    assert torch.equal(ident, plain)       # the identity map is flora_compress
+
+
+def test_compress_mapped_grouped_and_errors():
+    shapes = [(96, 160), (40, 72), (200, 64)]
+    r = 16
+    Gs = [rand(s, 4300 + l) for l, s in enumerate(shapes)]
+    states = [torch.zeros((n, r), device=DEV) for n, _ in shapes]
+    seeds = [4400 + l for l in range(len(shapes))]
+    mats = flora.matrices(shapes, grads=Gs, states=states, seeds=seeds)
+    flora.compress_mapped(mats, r, flora.F32, flora.INPUT_SQUARE, 0.0, 1.0)
+    sync()
+    for l in range(len(shapes)):
+        assert rel_fro(to64(states[l]), oracle.compress_mapped(to64(Gs[l]), r, seeds[l], "square")) < TOL_F32
+    with pytest.raises(flora.FloraError):
+        flora.compress_mapped(mats, r, flora.F32, 2, 0.0, 1.0)
+    with pytest.raises(flora.FloraError):
+        flora.compress_mapped(mats, 48, flora.F32, flora.INPUT_SQUARE, 0.0, 1.0)
+
+
 # the fp32 matrix-core kernel with shared columns, every rank, both gradient types, 1 / 2 / 4
 # column groups per workgroup, ragged parts, two launches in a row on one descriptor set
 @pytest.mark.parametrize("kg", [1, 2, 4])

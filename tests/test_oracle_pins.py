@@ -596,3 +596,43 @@ def test_projection_entries_match_the_stored_fixture():
         if row < 20000:
             A = oracle.materialise_A(seed, row + 1, r)
             assert list(A[row, :8]) == got
+
+
+# ---- compressed EMA of another statistic (closing remark of Section 2.3): the second moment
+
+def test_mapped_compress_is_the_matrix_product_of_the_squares():
+    rng = np.random.default_rng(61)
+    n, m, r, seed = 9, 37, 8, 4242
+    G, S0 = rng.standard_normal((n, m)), rng.standard_normal((n, r))
+    A = oracle.materialise_A(seed, m, r)
+    got = oracle.compress_mapped(G, r, seed, "square", state=S0, a=0.75, b=0.25)
+    np.testing.assert_allclose(got, 0.75 * S0 + 0.25 * (G * G) @ A, rtol=0, atol=1e-12)
+    # the sign of G cannot matter, and the identity map is plain compression
+    np.testing.assert_array_equal(oracle.compress_mapped(-G, r, seed, "square", state=S0, a=0.75, b=0.25), got)
+    np.testing.assert_array_equal(oracle.compress_mapped(G, r, seed, "identity"), oracle.compress(G, r, seed))
+    with pytest.raises(ValueError):
+        oracle.compress_mapped(G, r, seed, "cube")
+
+
+def test_compressed_second_moment_ema_decompresses_to_the_ema_without_bias():
+    # V_T = sum_t beta2^(T-t) (1 - beta2) G_t^2 ; its compressed form under one projection, decompressed
+    # and averaged over many independent projections, must approach V_T (E[A A^T] = I), and a single
+    # projection must be off by the relative error sqrt((m + 1) / r) that any n x m matrix suffers
+    rng = np.random.default_rng(62)
+    n, m, r, beta2, T = 6, 40, 8, 0.9, 5
+    Gs = [rng.standard_normal((n, m)) for _ in range(T)]
+    V = np.zeros((n, m))
+    for G in Gs:
+        V = beta2 * V + (1 - beta2) * G * G
+    trials, acc, err2 = 3000, np.zeros((n, m)), 0.0
+    for k in range(trials):
+        seed = oracle.derive_seed(99, 0, k)
+        S = np.zeros((n, r))
+        for G in Gs:
+            S = oracle.compress_mapped(G, r, seed, "square", state=S, a=beta2, b=1 - beta2)
+        est = oracle.decompress(S, m, seed)
+        acc += est
+        err2 += np.linalg.norm(est - V) ** 2
+    mean = acc / trials
+    assert np.linalg.norm(mean - V) / np.linalg.norm(V) < 4 * np.sqrt((m + 1) / r / trials)
+    assert err2 / trials / np.linalg.norm(V) ** 2 == pytest.approx((m + 1) / r, rel=0.1)
