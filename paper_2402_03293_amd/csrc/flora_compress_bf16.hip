@@ -229,7 +229,9 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 constexpr int kWBK = 64;             // columns of G per tile
 constexpr int kWLda = kWBK + 8;      // padded LDS row (bf16 elements): 144 bytes
 
-template <int CT, int RT, int MAP>   // per wave: CT 16-wide column tiles (RS = 16 CT), RT 16-row tiles; MAP 1: input squared
+// per wave: CT 16-wide column tiles (RS = 16 CT), RT 16-row tiles; MAP 1: input squared;
+// ONCE: r = RS, a single rank slice, so the launch reads G exactly once
+template <int CT, int RT, int MAP, bool ONCE>
 __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* __restrict__ mats,
                                                                  const WorkItem* __restrict__ items,
                                                                  const SeedArgs seeds, int R, float a, float b,
@@ -285,7 +287,9 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
         const bool ok = col < (uint32_t)col_end;
         const uint32_t coff = ((uint32_t)tile * kWBK + 32u * (uint32_t)s) * 2u;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) dst[rt][s] = buf_load_u4(rs, ok ? lane_off[rt] + coff : kOob);
+        // with one rank slice G is read once by the launch and streamed; with two, the second
+        // slice must find it in L2
+        for (int rt = 0; rt < RT; ++rt) dst[rt][s] = buf_load_u4<ONCE>(rs, ok ? lane_off[rt] + coff : kOob);
     };
 
     // 64 x RS normals per tile = 16 RS quads, NQ per thread: thread p takes quad index
@@ -505,11 +509,13 @@ hipError_t launch_wide(const MatDev* mats, const WorkItem* items, int nitems, co
 {
     const dim3 grid((unsigned)nitems), block(512);
     if (mt == 8) {
-        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else if (r == 128) hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP, false>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
     } else {
-        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 2, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
-        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2, MAP>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 2, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else if (r == 128) hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 2, MAP, false>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
     }
     return hipGetLastError();
 }

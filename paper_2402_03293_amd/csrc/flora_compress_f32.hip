@@ -134,9 +134,9 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 if (ESZ == 4) {
-                    dst[mt][c] = buf_load_f4(rs[mt], off);
+                    dst[mt][c] = buf_load_f4<true>(rs[mt], off);      // G is read once: streamed
                 } else {
-                    const v2u p2 = buf_load_u2(rs[mt], off);
+                    const v2u p2 = buf_load_u2<true>(rs[mt], off);
                     dst[mt][c] = v4f{bf16_bits_to_f32(p2.x & 0xffffu), bf16_bits_to_f32(p2.x >> 16),
                                      bf16_bits_to_f32(p2.y & 0xffffu), bf16_bits_to_f32(p2.y >> 16)};
                 }

@@ -112,6 +112,29 @@ __device__ __forceinline__ v2u buf_load_u2(rsrc_t r, uint32_t off)
 {
     return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
 }
+// The same with the non-temporal hint, for data a launch reads exactly once (the gradients):
+// the lines then do not displace what the caches hold for later (the weights the update has
+// just written, the state), which shortens the launches that follow an update.  A second pass
+// over the same data in the same launch (rank slices of a wide row block) would miss L2 with
+// it, so those launches use the plain loads.
+template <bool STREAM>
+__device__ __forceinline__ v4f buf_load_f4(rsrc_t r, uint32_t off)
+{
+    return __builtin_bit_cast(v4f, STREAM ? __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2)
+                                          : __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+}
+template <bool STREAM>
+__device__ __forceinline__ v4u buf_load_u4(rsrc_t r, uint32_t off)
+{
+    return STREAM ? __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2)
+                  : __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+}
+template <bool STREAM>
+__device__ __forceinline__ v2u buf_load_u2(rsrc_t r, uint32_t off)
+{
+    return STREAM ? __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2)
+                  : __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+}
 __device__ __forceinline__ float buf_load_f(rsrc_t r, uint32_t off)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
