@@ -279,19 +279,26 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
     };
     // four consecutive elements of W (fp32: 16 bytes, bf16: 8 bytes per lane); the store returns
     // the values as stored
+    // Cache policy of the n x m arrays this launch reads and writes once (weights, elementwise
+    // second moment), chosen by the host from their size: a set that fits the last-level cache
+    // stays there for the next step (plain accesses); a larger one is written, and a much larger
+    // one also read, with the non-temporal hint so that it does not push out what is reused.
+    const bool ld_stream = (p.wpolicy & 1) != 0, st_stream = (p.wpolicy & 2) != 0;
     auto load_w4 = [&](rsrc_t rw, uint32_t off) -> v4f {
-        if (sizeof(OT) == 4) return buf_load_f4(rw, off);
-        const v2u pk = buf_load_u2(rw, off);
+        if (sizeof(OT) == 4) return ld_stream ? buf_load_f4<true>(rw, off) : buf_load_f4<false>(rw, off);
+        const v2u pk = ld_stream ? buf_load_u2<true>(rw, off) : buf_load_u2<false>(rw, off);
         return v4f{bf16_bits_to_f32(pk.x & 0xffffu), bf16_bits_to_f32(pk.x >> 16),
                    bf16_bits_to_f32(pk.y & 0xffffu), bf16_bits_to_f32(pk.y >> 16)};
     };
     auto store_w4 = [&](rsrc_t rw, uint32_t off, v4f v) -> v4f {
         if (sizeof(OT) == 4) {
-            buf_store_f4(rw, off, v);
+            if (st_stream) buf_store_f4<true>(rw, off, v);
+            else buf_store_f4<false>(rw, off, v);
             return v;
         }
         const v2u pk = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
-        buf_store_u2(rw, off, pk);
+        if (st_stream) buf_store_u2<true>(rw, off, pk);
+        else buf_store_u2<false>(rw, off, pk);
         return v4f{bf16_bits_to_f32(pk.x & 0xffffu), bf16_bits_to_f32(pk.x >> 16),
                    bf16_bits_to_f32(pk.y & 0xffffu), bf16_bits_to_f32(pk.y >> 16)};
     };
@@ -316,7 +323,7 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
         if (kUsesV) {
             const rsrc_t rv = vrsrc(rb);
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp) pre.v[pp] = buf_load_f4(rv, voff(pp));
+            for (int pp = 0; pp < 4; ++pp) pre.v[pp] = ld_stream ? buf_load_f4<true>(rv, voff(pp)) : buf_load_f4<false>(rv, voff(pp));
         }
         if (MODE == kModeFactored) {
 #pragma unroll
@@ -427,7 +434,8 @@ __global__ __launch_bounds__(512) void decompress_bf16_vec_kernel(const MatDev* 
                 const v4f g2 = {a2 * a4.x * a4.x, a2 * a4.y * a4.y, a2 * a4.z * a4.z, a2 * a4.w * a4.w};
                 const v4f vn = {p.beta2 * v.x + omb * (g2.x + p.eps1), p.beta2 * v.y + omb * (g2.y + p.eps1),
                                 p.beta2 * v.z + omb * (g2.z + p.eps1), p.beta2 * v.w + omb * (g2.w + p.eps1)};
-                buf_store_f4(rv, voff(pp), vn);
+                if (st_stream) buf_store_f4<true>(rv, voff(pp), vn);
+                else buf_store_f4<false>(rv, voff(pp), vn);
                 const float u2 = ((g2.x / vn.x + g2.y / vn.y) + (g2.z / vn.z + g2.w / vn.w));
                 total += ok ? u2 : 0.f;
             }

@@ -64,6 +64,8 @@ struct DecompressParams {
     float coef;    // lr * alpha (SGD) or lr (factored, unfactored)
     float beta2;   // kModeFull1: decay of V
     float eps1;    // kModeFull1: added to Gt^2
+    int wpolicy;   // 16-byte-per-lane kernel: bit 0 weights / second moment read with the non-temporal
+                   // hint, bit 1 written with it (chosen from the size of the set, see choose_wpolicy)
 };
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -134,6 +136,18 @@ __device__ __forceinline__ v2u buf_load_u2(rsrc_t r, uint32_t off)
 {
     return STREAM ? __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2)
                   : __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+}
+template <bool STREAM>
+__device__ __forceinline__ void buf_store_f4(rsrc_t r, uint32_t off, v4f v)
+{
+    if (STREAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)off, 0, 2);
+    else __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)off, 0, 0);
+}
+template <bool STREAM>
+__device__ __forceinline__ void buf_store_u2(rsrc_t r, uint32_t off, v2u v)
+{
+    if (STREAM) __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)off, 0, 2);
+    else __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)off, 0, 0);
 }
 __device__ __forceinline__ float buf_load_f(rsrc_t r, uint32_t off)
 {
