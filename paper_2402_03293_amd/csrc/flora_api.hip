@@ -748,13 +748,17 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* c
 
 // Cache policy for the n x m arrays an update call reads and writes once per step (weights,
 // elementwise second moment), from their total size over the whole call.  The chip's last-level
-// cache is 256 MB: a set well inside it is found there again by the next step and is accessed
-// plainly; one that does not fit is written with the non-temporal hint (its dirty lines would
-// otherwise be written back under the next launches' reads); one several times larger is also
-// read with it, since nothing of it survives until the next step.  Measured on GPT-2 base
-// (340 MB of weights: whole step 0.193 -> 0.171 ms with streamed stores, 0.190 with both) and
-// GPT-2 XL (5.9 GB: 3.70 -> 3.58 ms with both, 3.69 with stores alone).
-static int choose_wpolicy(const flora_matrix_t* mats, int count, const flora_update_t* u, int wbf16)
+// cache is 256 MB.  A set well inside it is found there again by the next step and is accessed
+// plainly.  One that does not fit is written with the non-temporal hint (its dirty lines would
+// otherwise be written back under the next launches' reads); while it is less than about one
+// and a half times the cache, and the compress launches stream their gradients past the cache
+// (one rank slice: every rank but 256), part of it is still found there at the next step, so the
+// reads stay plain.  Anything larger is read with the hint as well: nothing of it survives.
+// Whole steps, same box (plain / streamed writes / both): GPT-2 base, r = 64, 324 MiB: 0.193 /
+// 0.171 / 0.190 ms; GPT-2 XL shapes: r = 64, 234 MiB 0.145 / 0.144 / 0.152, 469 MiB 0.308 / 0.300 /
+// 0.292, 1875 MiB 1.124 / 1.119 / 1.072; r = 256, 117 MiB 0.148 / 0.150 / 0.154, 234 MiB 0.272 /
+// 0.272 / 0.264, 5.6 GiB 3.70 / 3.69 / 3.58.
+static int choose_wpolicy(const flora_matrix_t* mats, int count, int r, const flora_update_t* u, int wbf16)
 {
     if (g_tune.update_wpolicy) return g_tune.update_wpolicy - 1;
     double bytes = 0.0;
@@ -762,7 +766,7 @@ static int choose_wpolicy(const flora_matrix_t* mats, int count, const flora_upd
     for (int l = 0; l < count; ++l) bytes += per * (double)mats[l].n * (double)mats[l].m;
     const double mib = bytes / (1024.0 * 1024.0);
     if (mib <= 192.0) return 0;
-    if (mib <= 768.0) return 2;
+    if (mib <= 400.0 && r != 256) return 2;
     return 3;
 }
 
@@ -962,7 +966,7 @@ int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype
     int st = check_update(mats, count, r, weight_dtype, u);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
-    const int wpolicy = choose_wpolicy(mats, count, u, weight_dtype == FLORA_BF16);
+    const int wpolicy = choose_wpolicy(mats, count, r, u, weight_dtype == FLORA_BF16);
     FLORA_FOR_CHUNKS(count, c0, cn) {
         st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, wpolicy, false, static_cast<hipStream_t>(hip_stream));
         if (st != FLORA_OK) return st;
@@ -981,7 +985,7 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
     std::lock_guard<std::mutex> guard(g_lock);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool next = do_transfer != 0;
-    const int wpolicy = choose_wpolicy(mats, count, u, weight_dtype == FLORA_BF16);
+    const int wpolicy = choose_wpolicy(mats, count, r, u, weight_dtype == FLORA_BF16);
     FLORA_FOR_CHUNKS(count, c0, cn) {
         if (next) {
             st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s);

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
     v4f stage[F4];
     fetch(stage, it.row0);
     TilePre<MODE> pre_cur, pre_nxt;
-    epilogue_fetch<MODE, OT>(pre_cur, M, it.row0, row_end, j, jok);
+    epilogue_fetch<MODE, OT>(pre_cur, M, p, it.row0, row_end, j, jok);
     stash(stage, 0);
     __syncthreads();
 
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void decompress_bf16_kernel(const MatDev* __re
         const bool more = rb + 32 < row_end;
         if (more) {
             fetch(stage, rb + 32);
-            epilogue_fetch<MODE, OT>(pre_nxt, M, rb + 32, row_end, j, jok);
+            epilogue_fetch<MODE, OT>(pre_nxt, M, p, rb + 32, row_end, j, jok);
         }
 
         f32x16 acc;

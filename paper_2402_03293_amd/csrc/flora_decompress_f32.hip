@@ -68,12 +68,12 @@ __global__ __launch_bounds__(256) void decompress_f32_kernel(const MatDev* __res
     v4f a_cur[H / 4], a_nxt[H / 4];
     TilePre<MODE> pre_cur, pre_nxt;
     load_state(a_cur, it.row0);
-    epilogue_fetch<MODE, OT>(pre_cur, M, it.row0, row_end, j, jok);
+    epilogue_fetch<MODE, OT>(pre_cur, M, p, it.row0, row_end, j, jok);
     for (long long rb = it.row0; rb < row_end; rb += 32) {
         const bool more = rb + 32 < row_end;
         if (more) {
             load_state(a_nxt, rb + 32);
-            epilogue_fetch<MODE, OT>(pre_nxt, M, rb + 32, row_end, j, jok);
+            epilogue_fetch<MODE, OT>(pre_nxt, M, p, rb + 32, row_end, j, jok);
         }
         f32x16 acc;
 #pragma unroll

@@ -4,6 +4,8 @@
 // 8 * (v / 4) + 4 * (lane / 32) + v % 4).  Shared by the fp32 and bf16
 // decompression kernels; Gt is never written to memory except by kModeOut.
 #pragma once
+#include <type_traits>
+
 #include "flora_internal.h"
 
 namespace flora {
@@ -66,9 +68,12 @@ __device__ __forceinline__ int tile_row(int v, int g) { return 8 * (v / 4) + 4 *
 // Addresses inside a tile are a workgroup-uniform base (first row of the tile) plus a 32-bit
 // per-lane element offset row * m + column: 33 m < 2^32 is guaranteed by the host (m <= 2^26).
 template <int MODE, typename OT>
-__device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev& M, long long rb,
-                                               long long row_end, long long j, bool jok)
+__device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev& M, const DecompressParams& p,
+                                               long long rb, long long row_end, long long j, bool jok)
 {
+    // cache policy of the weights and the second moment (uniform over the launch): one branch
+    // around each group of 16 loads or stores, not one per access
+    const bool ld_stream = (p.wpolicy & 1) != 0;
     const int g = (threadIdx.x & 63) >> 5;
     const uint32_t m32 = (uint32_t)M.m;
     // Clamped coordinates keep every load in bounds, so all 16 loads of a tile are issued
@@ -77,18 +82,34 @@ __device__ __forceinline__ void epilogue_fetch(TilePre<MODE>& pre, const MatDev&
     const int last = (int)(row_end - 1 - rb);          // last valid row of the tile, relative
     if (MODE == kModeSgd || MODE == kModeFactored || MODE == kModeFull2) {
         const OT* tb = reinterpret_cast<const OT*>(M.weight) + rb * M.m;
+        if (ld_stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
-            pre.w[v] = load_elem(tb + (rr * m32 + jc));
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+                pre.w[v] = load_elem<true>(tb + (rr * m32 + jc));
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+                pre.w[v] = load_elem<false>(tb + (rr * m32 + jc));
+            }
         }
     }
     if (MODE == kModeFull1 || MODE == kModeFull2) {
         const float* tb = M.vfull + rb * M.m;
+        if (ld_stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
-            pre.v[v] = ldg(tb + (rr * m32 + jc));
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+                pre.v[v] = load_elem<true>(tb + (rr * m32 + jc));
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t rr = (uint32_t)(tile_row(v, g) < last ? tile_row(v, g) : last);
+                pre.v[v] = load_elem<false>(tb + (rr * m32 + jc));
+            }
         }
     }
     if (MODE == kModeRms || MODE == kModeFactored) {
@@ -114,6 +135,7 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
     const long long n = M.n, m = M.m;
     const int rows_here = (int)((row_end - rb < 32) ? row_end - rb : 32);
     const uint32_t m32 = (uint32_t)m, j32 = (uint32_t)j;
+    const bool st_stream = (p.wpolicy & 2) != 0;    // see epilogue_fetch
     float rowsq[16];
     if (MODE == kModeOut) {
         OT* ob = reinterpret_cast<OT*>(M.out) + rb * m;
@@ -128,10 +150,15 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
         }
     } else if (MODE == kModeSgd) {
         OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
+        auto sweep = [&](auto stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (jok && tile_row(v, g) < rows_here)
-                store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32), pre.w[v] - p.coef * acc[v]);
+            for (int v = 0; v < 16; ++v)
+                if (jok && tile_row(v, g) < rows_here)
+                    store_elem<decltype(stream)::value>(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
+                                                        pre.w[v] - p.coef * acc[v]);
+        };
+        if (st_stream) sweep(std::true_type{});
+        else sweep(std::false_type{});
     } else if (MODE == kModeStats) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -146,32 +173,44 @@ __device__ __forceinline__ void epilogue_tile(const f32x16& acc, const TilePre<M
             if (jok && tile_row(v, g) < rows_here) e.colsum += acc[v] * acc[v] * e.kfac / pre.rs[v];
     } else if (MODE == kModeFactored) {
         OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
+        auto sweep = [&](auto stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (jok && tile_row(v, g) < rows_here) {
-                const float wn = store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
-                                            pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v]);
-                e.colsum = __builtin_fmaf(wn, wn, e.colsum);     // of the value as stored
-            }
+            for (int v = 0; v < 16; ++v)
+                if (jok && tile_row(v, g) < rows_here) {
+                    const float wn = store_elem<decltype(stream)::value>(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
+                                                                         pre.w[v] - e.kfac * rsqrtf(pre.rs[v]) * acc[v]);
+                    e.colsum = __builtin_fmaf(wn, wn, e.colsum);     // of the value as stored
+                }
+        };
+        if (st_stream) sweep(std::true_type{});
+        else sweep(std::false_type{});
     } else if (MODE == kModeFull1) {
         float* vb = M.vfull + rb * m;
+        auto sweep = [&](auto stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (jok && tile_row(v, g) < rows_here) {
-                const float gt = p.alpha * acc[v];
-                const float vn = p.beta2 * pre.v[v] + (1.f - p.beta2) * (gt * gt + p.eps1);
-                stg(vb + ((uint32_t)tile_row(v, g) * m32 + j32), vn);
-                e.colsum += gt * gt / vn;
-            }
+            for (int v = 0; v < 16; ++v)
+                if (jok && tile_row(v, g) < rows_here) {
+                    const float gt = p.alpha * acc[v];
+                    const float vn = p.beta2 * pre.v[v] + (1.f - p.beta2) * (gt * gt + p.eps1);
+                    store_elem<decltype(stream)::value>(vb + ((uint32_t)tile_row(v, g) * m32 + j32), vn);
+                    e.colsum += gt * gt / vn;
+                }
+        };
+        if (st_stream) sweep(std::true_type{});
+        else sweep(std::false_type{});
     } else if (MODE == kModeFull2) {
         OT* wb = reinterpret_cast<OT*>(M.weight) + rb * m;
+        auto sweep = [&](auto stream) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (jok && tile_row(v, g) < rows_here) {
-                const float wn = store_elem(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
-                                            pre.w[v] - e.kfac * rsqrtf(pre.v[v]) * acc[v]);
-                e.colsum = __builtin_fmaf(wn, wn, e.colsum);
-            }
+            for (int v = 0; v < 16; ++v)
+                if (jok && tile_row(v, g) < rows_here) {
+                    const float wn = store_elem<decltype(stream)::value>(wb + ((uint32_t)tile_row(v, g) * m32 + j32),
+                                                                         pre.w[v] - e.kfac * rsqrtf(pre.v[v]) * acc[v]);
+                    e.colsum = __builtin_fmaf(wn, wn, e.colsum);
+                }
+        };
+        if (st_stream) sweep(std::true_type{});
+        else sweep(std::false_type{});
     }
     if (MODE == kModeStats) {
         // row sums over this wave's 32 columns, then over the 4 waves in a fixed order

@@ -64,8 +64,8 @@ struct DecompressParams {
     float coef;    // lr * alpha (SGD) or lr (factored, unfactored)
     float beta2;   // kModeFull1: decay of V
     float eps1;    // kModeFull1: added to Gt^2
-    int wpolicy;   // 16-byte-per-lane kernel: bit 0 weights / second moment read with the non-temporal
-                   // hint, bit 1 written with it (chosen from the size of the set, see choose_wpolicy)
+    int wpolicy;   // update passes: bit 0 weights / second moment read with the non-temporal hint,
+                   // bit 1 written with it (chosen from the size of the set, see choose_wpolicy)
 };
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -188,15 +188,35 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b)
 {
     return __builtin_bit_cast(float, b << 16);
 }
-// One element of an n x m array of fp32 or bf16 (weights, decompressed gradients): loads give the
-// value as fp32, stores round to nearest even and return the value that was stored.
+// One element of an n x m array of fp32 or bf16 (weights), as fp32.
 __device__ __forceinline__ float load_elem(const float* p) { return *(const FLORA_GLOBAL float*)p; }
 __device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_bits_to_f32(*(const FLORA_GLOBAL uint16_t*)p); }
-__device__ __forceinline__ float store_elem(float* p, float v) { *(FLORA_GLOBAL float*)p = v; return v; }
+// Loads and stores with the non-temporal hint when STREAM is set (cache policy of the update
+// passes); stores round to nearest even and return the value that was stored.
+template <bool STREAM>
+__device__ __forceinline__ float load_elem(const float* p)
+{
+    return STREAM ? __builtin_nontemporal_load((const FLORA_GLOBAL float*)p) : *(const FLORA_GLOBAL float*)p;
+}
+template <bool STREAM>
+__device__ __forceinline__ float load_elem(const uint16_t* p)
+{
+    return bf16_bits_to_f32(STREAM ? __builtin_nontemporal_load((const FLORA_GLOBAL uint16_t*)p)
+                                   : *(const FLORA_GLOBAL uint16_t*)p);
+}
+template <bool STREAM>
+__device__ __forceinline__ float store_elem(float* p, float v)
+{
+    if (STREAM) __builtin_nontemporal_store(v, (FLORA_GLOBAL float*)p);
+    else *(FLORA_GLOBAL float*)p = v;
+    return v;
+}
+template <bool STREAM>
 __device__ __forceinline__ float store_elem(uint16_t* p, float v)
 {
     const uint32_t b = f32_to_bf16_bits(v);
-    *(FLORA_GLOBAL uint16_t*)p = (uint16_t)b;
+    if (STREAM) __builtin_nontemporal_store((uint16_t)b, (FLORA_GLOBAL uint16_t*)p);
+    else *(FLORA_GLOBAL uint16_t*)p = (uint16_t)b;
     return bf16_bits_to_f32(b);
 }
 

@@ -339,3 +339,40 @@ def test_weight_sumsq_bf16_and_vector_kernel_tails():
     sync()
     for i, W in enumerate(Ws):
         assert float(out[i, 0]) == pytest.approx(float((to64(W) ** 2).sum()), rel=2e-6)
+
+
+# the cache policy of the weights (plain / streamed reads / streamed writes / both) is a hint to the
+# memory system and nothing else: every policy gives the same bits, for every rule, in the 4-byte
+# and the 16-byte-per-lane kernels
+@pytest.mark.parametrize("rule", ["sgd", "factored", "unfactored"])
+@pytest.mark.parametrize("n,m,r,wdt", [(130, 200, 16, "f32"), (97, 1001, 64, "f32"), (257, 264, 256, "f32"),
+                                       (257, 264, 128, "bf16"), (70, 130, 32, "bf16")])
+def test_update_cache_policies_give_the_same_bits(n, m, r, wdt, rule):
+    dt = torch.float32 if wdt == "f32" else torch.bfloat16
+    fd = flora.F32 if wdt == "f32" else flora.BF16
+    seed = 5100 + n + m + r
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    W0 = torch.randn(n, m, generator=g).to(dt).to(DEV)
+    S = torch.randn(n, r, generator=g).to(DEV)
+    out = []
+    for policy in (1, 2, 3, 4):
+        W = W0.clone()
+        kw = dict(weights=[W], states=[S.clone()], seeds=[seed])
+        if rule == "factored":
+            kw.update(row_stats=[torch.zeros(n, device=DEV)], col_stats=[torch.zeros(m, device=DEV)])
+            upd = flora.factored_update(1e-2, 1.0, 0.0, 1e-30, 1.0)
+        elif rule == "unfactored":
+            kw.update(second_moments=[torch.full((n, m), 0.5, device=DEV)])
+            upd = flora.unfactored_update(1e-2, 1.0, 0.5, 1e-30, 1.0)
+        else:
+            upd = flora.sgd_update(1e-2, 1.0)
+        flora.set_tuning("update_wpolicy", policy)
+        try:
+            flora.apply_update(flora.matrices([(n, m)], **kw), r, fd, upd)
+            torch.cuda.synchronize()
+        finally:
+            flora.set_tuning("update_wpolicy", 0)
+        out.append(W.clone())
+        assert not torch.equal(W, W0)
+    for W in out[1:]:
+        assert torch.equal(W, out[0])
