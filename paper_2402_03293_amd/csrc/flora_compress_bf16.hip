@@ -219,7 +219,9 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 //     memory straight into its operand registers and is never shared;
 //   * the registers of a tile are refilled with the tile two steps ahead as soon
 //     as the MFMAs that read them have been issued (two register sets, loop
-//     unrolled by two), so about one and a half tiles are in flight per wave;
+//     unrolled by two), so about one and a half tiles are in flight per wave
+//     (with one rank slice G is read once and streamed past the caches, and a tile's
+//     two halves are then refilled together);
 //   * the 64 x RS slice of A is regenerated once per tile by all 512 threads
 //     into LDS (bf16, transposed, double buffered); waves 0-3 generate while waves
 //     4-7 multiply and the other way round, so that the two waves of a SIMD
@@ -351,7 +353,11 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
                 bv = bn;
             }
             __builtin_amdgcn_sched_barrier(0);
-            load_half(gt, tile + 2, s);
+            // Streamed loads are not kept in L2: the two 64-byte halves of a row's 128-byte line
+            // are then asked for together, at the end of the tile, or the second would often
+            // fetch the line from memory again.
+            if (!ONCE) load_half(gt, tile + 2, s);
+            else if (s == 1) { load_half(gt, tile + 2, 0); load_half(gt, tile + 2, 1); }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
