@@ -177,11 +177,17 @@ def main():
     if args.momentum:
         alpha_u, zero_after = 1.0, False     # the momentum is not reset and its decompression carries no 1/tau
 
+    # calls that cover a few matrices each tell the library how large the whole step's set of weights is
+    step_mib = 0.0
+    if args.layerwise:
+        step_mib = sum(n * m for n, m in wl.shapes) * (4 + (4 if rule == "unfactored" else 0)) / 2.0 ** 20
+
     def adafactor_update(t):
         # step t = 1, 2, ... of the published schedules, relative to the parameter scale
         rho, beta2 = flora.adafactor_schedule(t)
         mk = flora.factored_update if rule == "adafactor" else flora.unfactored_update
-        return mk(rho, alpha_u, beta2, 1e-30, 1.0, zero_state_after=zero_after, scale_parameter=True, eps2=1e-3)
+        return mk(rho, alpha_u, beta2, 1e-30, 1.0, zero_state_after=zero_after, scale_parameter=True, eps2=1e-3,
+                  step_weight_mib=step_mib)
 
     if rule in ("adafactor", "unfactored"):
         flora.weight_sumsq(mats_sets[0], flora.F32, stream)     # once: the updates carry it from here on
@@ -193,6 +199,8 @@ def main():
         upd = flora.sgd_update(wl.lr, 1.0 / wl.tau)
     else:
         upd = flora.sgd_update(wl.lr, 1.0)
+
+    upd.step_weight_mib = step_mib
 
     upd_mom = None
     if args.momentum:

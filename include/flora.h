@@ -109,6 +109,12 @@ typedef struct flora_update {
     int   scale_parameter;   /* Adafactor rules, non-zero: the step is lr * max(eps2, RMS(W)), lr then
                                 being the relative step size rho_t; ignored by FLORA_RULE_SGD           */
     float eps2;              /* floor of the parameter scale RMS(W)                                     */
+    float step_weight_mib;   /* 0 when this call updates everything the caller's optimizer step updates;
+                                otherwise (one call per layer, say) the MiB of weights, plus elementwise
+                                second moments, that the whole step passes through the library: the
+                                library picks the cache policy of these arrays from the larger of this
+                                and the call's own size (a set beyond the 256 MB last-level cache is
+                                streamed past it).  Never changes results.  >= 0 and finite           */
 } flora_update_t;
 
 /* Compression (Algorithm 1, compression line: a = b = 1;  Algorithm 2, EMA

@@ -764,7 +764,8 @@ static int choose_wpolicy(const flora_matrix_t* mats, int count, int r, const fl
     double bytes = 0.0;
     const double per = (wbf16 ? 2.0 : 4.0) + (u->rule == FLORA_RULE_UNFACTORED ? 4.0 : 0.0);
     for (int l = 0; l < count; ++l) bytes += per * (double)mats[l].n * (double)mats[l].m;
-    const double mib = bytes / (1024.0 * 1024.0);
+    // a caller that spreads one optimizer step over several calls says how large the whole set is
+    const double mib = std::max(bytes / (1024.0 * 1024.0), (double)u->step_weight_mib);
     if (mib <= 192.0) return 0;
     if (mib <= 400.0 && r != 256) return 2;
     return 3;
@@ -862,6 +863,7 @@ static int check_update(const flora_matrix_t* mats, int count, int r, flora_dtyp
     if (ada && (!(u->beta2 >= 0.f && u->beta2 <= 1.f) || !(u->clip_d >= 0.f) || !(u->eps1 >= 0.f)))
         return FLORA_ERR_INVALID;
     if (ada && u->scale_parameter && !(u->eps2 >= 0.f)) return FLORA_ERR_INVALID;
+    if (!(u->step_weight_mib >= 0.f) || !std::isfinite(u->step_weight_mib)) return FLORA_ERR_INVALID;
     for (int l = 0; l < count; ++l) {
         if (!mats[l].weight || !aligned16(mats[l].weight) || mats[l].weight == (void*)mats[l].state)
             return FLORA_ERR_INVALID;

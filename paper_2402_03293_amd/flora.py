@@ -55,6 +55,7 @@ class Update(ctypes.Structure):
         ("zero_state_after", ctypes.c_int),
         ("scale_parameter", ctypes.c_int),
         ("eps2", ctypes.c_float),
+        ("step_weight_mib", ctypes.c_float),
     ]
 
 
@@ -265,22 +266,22 @@ def workspace_bytes(mats, r: int) -> int:
     return int(lib().flora_workspace_bytes(mats, len(mats), r))
 
 
-def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False) -> Update:
-    return Update(RULE_SGD, lr, alpha, 0.0, 0.0, 0.0, int(zero_state_after), 0, 0.0)
+def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False, step_weight_mib: float = 0.0) -> Update:
+    return Update(RULE_SGD, lr, alpha, 0.0, 0.0, 0.0, int(zero_state_after), 0, 0.0, step_weight_mib)
 
 
 def factored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
                     zero_state_after: bool = False, scale_parameter: bool = False,
-                    eps2: float = 1e-3) -> Update:
+                    eps2: float = 1e-3, step_weight_mib: float = 0.0) -> Update:
     return Update(RULE_FACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after),
-                  int(scale_parameter), eps2)
+                  int(scale_parameter), eps2, step_weight_mib)
 
 
 def unfactored_update(lr: float, alpha: float, beta2: float, eps1: float, clip_d: float,
                       zero_state_after: bool = False, scale_parameter: bool = False,
-                      eps2: float = 1e-3) -> Update:
+                      eps2: float = 1e-3, step_weight_mib: float = 0.0) -> Update:
     return Update(RULE_UNFACTORED, lr, alpha, beta2, eps1, clip_d, int(zero_state_after),
-                  int(scale_parameter), eps2)
+                  int(scale_parameter), eps2, step_weight_mib)
 
 
 def weight_sumsq(mats, weight_dtype: int = F32, stream=None):

@@ -76,6 +76,9 @@ class Flora:
         self.seed = [flora.derive_seed(seed, l, 0) for l in range(count)]
         self._handles = []
         self._sumsq_ready = False
+        # what one optimizer step moves through the update passes, for calls that cover only part of it
+        per = self.params[0].element_size() + (4 if rule == "unfactored" else 0)
+        self.step_weight_mib = sum(n * m for n, m in self.shapes) * per / 2.0 ** 20
 
     # ------------------------------------------------------------------ descriptors
     def _descriptors(self, idx):
@@ -106,12 +109,13 @@ class Flora:
 
     def _update_struct(self, t: int, last_of_cycle_alpha: float, zero_after: bool):
         if self.rule == "sgd":
-            return flora.sgd_update(self.lr, last_of_cycle_alpha, zero_state_after=zero_after)
+            return flora.sgd_update(self.lr, last_of_cycle_alpha, zero_state_after=zero_after,
+                                    step_weight_mib=self.step_weight_mib)
         rho, beta2 = flora.adafactor_schedule(t)
         lr = rho if self.lr is None else self.lr
         mk = flora.factored_update if self.rule == "adafactor" else flora.unfactored_update
         return mk(lr, last_of_cycle_alpha, beta2, self.eps1, self.clip_d, zero_state_after=zero_after,
-                  scale_parameter=self.scale_parameter, eps2=self.eps2)
+                  scale_parameter=self.scale_parameter, eps2=self.eps2, step_weight_mib=self.step_weight_mib)
 
     # ------------------------------------------------------------------ one call for a set of matrices
     def _run(self, idx, stream=None):

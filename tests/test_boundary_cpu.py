@@ -29,9 +29,10 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(flora.Matrix) == 5 * 8 + 2 * 8 + 2 * 8 + 2 * 8
-    assert ctypes.sizeof(flora.Update) == 9 * 4
+    assert ctypes.sizeof(flora.Update) == 10 * 4
     assert flora.Matrix.second_moment.offset == 72 and flora.Matrix.weight_sumsq.offset == 80
     assert flora.Update.scale_parameter.offset == 28 and flora.Update.eps2.offset == 32
+    assert flora.Update.step_weight_mib.offset == 36
 
 
 def test_status_strings_and_version():
@@ -96,6 +97,9 @@ def test_update_validation():
     assert L.flora_apply_update(ok, 1, 16, 5, ctypes.byref(sgd), None) == flora.ERR_INVALID
     bad_rule = flora.Update(9, 0.1, 1.0, 0, 0, 0, 0, 0, 0)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(bad_rule), None) == flora.ERR_INVALID
+    for bad in (-1.0, float("inf"), float("nan")):
+        assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(flora.sgd_update(0.1, step_weight_mib=bad)),
+                                    None) == flora.ERR_INVALID
     fac = flora.factored_update(0.1, 1.0, 0.0, 1e-30, 1.0)
     assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(fac), None) == flora.ERR_INVALID  # no R, K
     neg = flora.factored_update(0.1, 1.0, 1.5, 1e-30, 1.0)
