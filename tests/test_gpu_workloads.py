@@ -290,3 +290,38 @@ def test_workload4_shapes_whole_adafactor_step(rule):
     for l in range(0, count, 37):
         assert float(ss[l, 0]) == pytest.approx(float((W[l].double() ** 2).sum()), rel=5e-6)
         assert bool(torch.isfinite(W[l]).all())
+
+
+@pytest.mark.parametrize("index", [2, 5])
+def test_compressed_second_moment_at_full_size_sampled_rows(index):
+    """flora_compress_mapped with the square map over a whole workload set in one grouped launch
+    (fp32 path on workload 2, wide bf16 kernel with two rank slices on workload 5): two steps of the
+    EMA, compared row by row with the oracle on sampled rows of a few matrices."""
+    wl = workloads.workload(index)
+    r, count = wl.r, len(wl.shapes)
+    fd = flora.F32 if wl.grad_dtype == "f32" else flora.BF16
+    rng = np.random.default_rng(100 + index)
+    gen = workloads.make_generator(wl.seed, DEV)
+    Gsets = [workloads.make_grad_set(wl, gen, DEV) for _ in range(2)]
+    V = [torch.zeros((n, r), device=DEV) for n, _ in wl.shapes]
+    seeds = flora.derive_seeds(77, 0, count, 0)
+    beta2 = 0.8
+    for t, G in enumerate(Gsets):
+        mats = flora.matrices(wl.shapes, grads=G, states=V, seeds=seeds)
+        flora.compress_mapped(mats, r, fd, flora.INPUT_SQUARE, 0.0 if t == 0 else beta2, 1.0 - beta2)
+    torch.cuda.synchronize()
+    check = first_of_each_shape(wl.shapes) + [count - 1]
+    worst = 0.0
+    for l in check:
+        n, m = wl.shapes[l]
+        rows = sample_rows(n, rng)
+        idx = torch.as_tensor(rows, device=DEV)
+        ref = np.zeros((len(rows), r))
+        for t, G in enumerate(Gsets):
+            ref = oracle.compress_mapped(to64(G[l][idx]), r, int(seeds[l]), "square", state=ref,
+                                         a=0.0 if t == 0 else beta2, b=1.0 - beta2)
+        got = to64(V[l][idx])
+        per_row = np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)
+        worst = max(worst, float(per_row.max()))
+    print("workload %d: worst row err of the compressed second moment %.2e" % (index, worst))
+    assert worst < (TOL_F32 if r <= 32 else TOL_BF16)
