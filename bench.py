@@ -53,6 +53,9 @@ def parse_args():
                          "(beta 0.9) and update from that.  folded: accumulate into C under one projection, "
                          "then M <- beta M + ((1-beta)/tau) C A_c^T A_m (flora_transfer_accumulate); direct: one "
                          "projection for both, every micro-batch is compressed straight into M")
+    ap.add_argument("--weights", default="f32", choices=["f32", "bf16"],
+                    help="dtype of the weights (the workloads are defined with fp32 weights; bf16 weights are "
+                         "updated in fp32 and rounded to nearest even when stored)")
     ap.add_argument("--input-map", default=None, choices=["square"],
                     help="compress the elementwise square of the gradients (flora_compress_mapped: the compressed "
                          "EMA of the second moment) instead of the gradients; same launches otherwise")
@@ -107,6 +110,10 @@ def main():
         nsets = max(4, min(8, int(2e9 // max(1, wl.grad_bytes)) + 1))
     grad_sets = [workloads.make_grad_set(wl, gen, dev) for _ in range(nsets)]
     W = workloads.make_weight_set(wl, gen, dev)
+    wdt, wbytes = flora.F32, 4
+    if args.weights == "bf16":
+        W = [w.to(torch.bfloat16) for w in W]
+        wdt, wbytes = flora.BF16, 2
     states = [torch.zeros((n, r), device=dev, dtype=torch.float32) for n, _ in shapes]
     row_stats = col_stats = second = sumsq = None
     rule = args.rule or wl.rule
@@ -180,7 +187,7 @@ def main():
     # calls that cover a few matrices each tell the library how large the whole step's set of weights is
     step_mib = 0.0
     if args.layerwise:
-        step_mib = sum(n * m for n, m in wl.shapes) * (4 + (4 if rule == "unfactored" else 0)) / 2.0 ** 20
+        step_mib = sum(n * m for n, m in wl.shapes) * (wbytes + (4 if rule == "unfactored" else 0)) / 2.0 ** 20
 
     def adafactor_update(t):
         # step t = 1, 2, ... of the published schedules, relative to the parameter scale
@@ -190,7 +197,7 @@ def main():
                   step_weight_mib=step_mib)
 
     if rule in ("adafactor", "unfactored"):
-        flora.weight_sumsq(mats_sets[0], flora.F32, stream)     # once: the updates carry it from here on
+        flora.weight_sumsq(mats_sets[0], wdt, stream)     # once: the updates carry it from here on
         upd = adafactor_update(1)
     elif wl.rule == "factored":
         ex = wl.extra
@@ -259,7 +266,7 @@ def main():
                 timed("transfer", lambda: flora.transfer_accumulate(mt, r, beta, (1.0 - beta) / wl.tau, mom, stream))
             mt = mats_mom[0]
             u_ = upd if rule in ("adafactor", "unfactored") else upd_mom
-            timed("update", lambda: flora.apply_update(mt, r, flora.F32, u_, stream))
+            timed("update", lambda: flora.apply_update(mt, r, wdt, u_, stream))
             epoch += 1
             seeds = flora.derive_seeds(gseed, 0, count, epoch)
             set_seeds(seeds)
@@ -271,7 +278,7 @@ def main():
                 a_ = 0.0 if i == 0 else 1.0
                 timed("compress", lambda: do_compress(mt, a_, 1.0))
             mt = mats_sets[0]
-            timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
+            timed("update", lambda: flora.apply_update(mt, r, wdt, upd, stream))
             epoch += 1
             seeds = flora.derive_seeds(gseed, 0, count, epoch)
             set_seeds(seeds)
@@ -292,14 +299,14 @@ def main():
                 def all_layers():
                     for gi in range(len(groups) - 1, -1, -1):  # the order gradients appear in backward
                         flora.fields(ones[gi])["seed"][:] = seeds[groups[gi][0]:groups[gi][-1] + 1]
-                        flora.fused_step(ones[gi], r, gdt, flora.F32, wl.beta, 1.0 - wl.beta, False, upd, stream)
+                        flora.fused_step(ones[gi], r, gdt, wdt, wl.beta, 1.0 - wl.beta, False, upd, stream)
                 timed("layerwise", all_layers)
                 tstate["t"] += 1
                 return
             mt = mats_sets[tstate["gi"] % nsets]
             tstate["gi"] += 1
             timed("compress", lambda: do_compress(mt, wl.beta, 1.0 - wl.beta))
-            timed("update", lambda: flora.apply_update(mt, r, flora.F32, upd, stream))
+            timed("update", lambda: flora.apply_update(mt, r, wdt, upd, stream))
             tstate["t"] += 1
 
     if args.calibrate_copy:
@@ -330,8 +337,8 @@ def main():
     E, S = wl.elements, wl.state_elements
     alg_bytes = {
         "compress": gbytes * E + 8 * S,
-        "update": {"sgd": 4 * S + 8 * E, "factored": 3 * 4 * S + 8 * E, "adafactor": 3 * 4 * S + 8 * E,
-                   "unfactored": 2 * 4 * S + 20 * E}[rule],
+        "update": {"sgd": 4 * S + 2 * wbytes * E, "factored": 3 * 4 * S + 2 * wbytes * E,
+                   "adafactor": 3 * 4 * S + 2 * wbytes * E, "unfactored": 2 * 4 * S + (12 + 2 * wbytes) * E}[rule],
         "transfer": 8 * S if not args.momentum else 12 * S,     # folded: reads C, reads and writes M
     }
     alg_bytes["layerwise"] = alg_bytes["compress"] + alg_bytes["update"]
@@ -380,7 +387,7 @@ def main():
                    "algorithm": wl.algorithm, "tau": wl.tau if wl.algorithm == 1 else None,
                    "beta": wl.beta if wl.algorithm == 2 else None,
                    "kappa": wl.kappa if wl.algorithm == 2 else None,
-                   "rule": rule, "momentum_from_accumulator": args.momentum, "input_map": args.input_map, "layerwise": args.layerwise, "grad_sets_in_ring": nsets,
+                   "rule": rule, "momentum_from_accumulator": args.momentum, "input_map": args.input_map, "weights": args.weights, "layerwise": args.layerwise, "grad_sets_in_ring": nsets,
                    "grad_bytes_per_step": grad_bytes_step},
         "roofline": roofline,
         "kernels": kern,
