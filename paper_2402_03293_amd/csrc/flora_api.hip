@@ -845,7 +845,7 @@ static int sumsq_chunk(const flora_matrix_t* mats, int count, int wbf16, hipStre
 }
 
 // ---- validation of whole calls ----
-static int check_grads(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype)
+static int check_grads(const flora_matrix_t* mats, int count, flora_dtype_t grad_dtype)
 {
     if (!dtype_ok((int)grad_dtype)) return FLORA_ERR_INVALID;
     for (int l = 0; l < count; ++l)
@@ -895,7 +895,7 @@ int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t g
 {
     int st = check_common(mats, count, r);
     if (st != FLORA_OK) return st;
-    st = check_grads(mats, count, r, grad_dtype);
+    st = check_grads(mats, count, grad_dtype);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
@@ -911,7 +911,7 @@ int flora_compress_mapped(const flora_matrix_t* mats, int count, int r, flora_dt
     if ((int)map != FLORA_INPUT_IDENTITY && (int)map != FLORA_INPUT_SQUARE) return FLORA_ERR_INVALID;
     int st = check_common(mats, count, r);
     if (st != FLORA_OK) return st;
-    st = check_grads(mats, count, r, grad_dtype);
+    st = check_grads(mats, count, grad_dtype);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     FLORA_FOR_CHUNKS(count, c0, cn) {
@@ -986,7 +986,7 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
 {
     int st = check_update(mats, count, r, weight_dtype, u);
     if (st != FLORA_OK) return st;
-    st = check_grads(mats, count, r, grad_dtype);
+    st = check_grads(mats, count, grad_dtype);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
