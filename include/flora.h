@@ -251,7 +251,7 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
  * (value 0 restores the default).  Names: "compress_f32_kgroups" (1, 2, 4: column groups per
  * workgroup in the fp32 compress kernel), "compress_f32_mt" (1, 2: rows per workgroup / 64 in
  * the same kernel), "compress_bf16_mt" (1, 2, 4: rows per workgroup / 128
- * in the bf16 compress kernel; 8 / 16: its wide variant with 512 / 256 rows, used only when
+ * in the bf16 compress kernel; 8 / 16 / 32: its wide variant with 512 / 256 / 128 rows, used only when
  * every m is a multiple of 8), "compress_splitk_cols" (a multiple of 64: in the wide variant,
  * share the columns of a row block between workgroups of about this many columns each), "decompress_rows" (a multiple of 32: rows per workgroup in the
  * decompress / update kernels), "decompress_vec" (1: always the 4-byte-per-lane kernel at

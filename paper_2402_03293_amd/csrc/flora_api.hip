@@ -102,7 +102,7 @@ struct Plan {
 // Launch-shape knobs, settable through flora_set_tuning (0 = let the library choose).
 struct Tuning {
     int compress_f32_kgroups = 0;   // column groups per workgroup in the fp32 compress kernel: 1, 2 or 4
-    int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4
+    int compress_bf16_mt = 0;       // bf16 compress: rows per workgroup / 128: 1, 2 or 4; wide kernel: 8, 16, 32
     int compress_f32_mt = 0;        // fp32 compress: rows per workgroup / 64: 1 or 2
     int compress_splitk_cols = 0;   // wide bf16 compress: columns per part when a row block's columns are shared
     int decompress_rows = 0;        // decompress / update: rows per workgroup, a multiple of 32
@@ -183,7 +183,7 @@ void build_compress_f32_items(Plan& p)
 
 void build_compress_bf16_items(Plan& p)
 {
-    // The wide kernel (512 or 256 rows per workgroup, rank slices of 128) regenerates A least
+    // The wide kernel (512, 256 or 128 rows per workgroup, rank slices of 128) regenerates A least
     // often; it needs 16-byte aligned rows of G.  A launch should give the chip at least one
     // and a half workgroups per compute unit: if whole row blocks do not, the columns of a row
     // block are shared between up to a few workgroups (partial products, combined by the last
@@ -220,6 +220,15 @@ void build_compress_bf16_items(Plan& p)
                     kc = kc_opt[ki];
                     found = true;
                 }
+        // Launches over one or two matrices cannot fill the chip either way; what counts then is
+        // how long the longest workgroup runs.  Fewer than about 130 workgroups of 256 rows: rows
+        // are taken 128 at a time, and below about 150 of those the columns in parts of 384
+        // (single matrices of GPT-2 XL and T5-3B shapes: 23-47 -> 21-37 us at r = 256, 21-38 ->
+        // 14-26 us at r = 64; taller or wider ones lose with smaller pieces and keep 256 x 768).
+        if (!found && wide_wgs(256, 768) < 130) {
+            mt = 32;
+            kc = wide_wgs(128, 768) < 150 ? 384 : 768;
+        }
         if (g_tune.compress_splitk_cols) kc = g_tune.compress_splitk_cols;
     } else for (; mt > 1; mt >>= 1) {
         long long wgs = 0;
@@ -231,7 +240,7 @@ void build_compress_bf16_items(Plan& p)
     const bool wide = mt >= 8;
     if (!wide) kc = 0;
     p.mt = mt;
-    const int rows_per_wg = (mt == 8) ? 512 : (mt == 16) ? 256 : 128 * mt;
+    const int rows_per_wg = (mt == 8) ? 512 : (mt == 16) ? 256 : (mt == 32) ? 128 : 128 * mt;
     const int slice_w = wide ? wide_slice : kCompressBf16Slice;
     const int S = p.r / slice_w;
     struct Block { int mat, row0, rows, rblock; long long m; };
@@ -1140,7 +1149,7 @@ int flora_set_tuning(const char* name, int value)
         if (value < 0 || (value % 64) != 0) return FLORA_ERR_INVALID;
         g_tune.compress_splitk_cols = value;
     } else if (std::strcmp(name, "compress_bf16_mt") == 0) {
-        if (!pow2_124 && value != 8 && value != 16) return FLORA_ERR_INVALID;
+        if (!pow2_124 && value != 8 && value != 16 && value != 32) return FLORA_ERR_INVALID;
         g_tune.compress_bf16_mt = value;
     } else if (std::strcmp(name, "decompress_vec") == 0) {
         if (value < 0 || value > 2) return FLORA_ERR_INVALID;

@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void compress_bf16_kernel(const MatDev* __rest
 
 
 // ---------------------------------------------------------------------------
-// Wide variant: 8 waves own 512 rows x RS rank columns (RS = 128, or 64 at
+// Wide variant: 8 waves own 512 (or 256, 128) rows x RS rank columns (RS = 128, or 64 at
 // r = 64) and sweep m in tiles of 64 columns.  It needs rows of G that start on
 // 16-byte boundaries (m % 8 == 0); the kernel above remains for everything else.
 //
@@ -514,7 +514,11 @@ hipError_t launch_wide(const MatDev* mats, const WorkItem* items, int nitems, co
                        float a, float b, float* partials, uint32_t* counters, hipStream_t s)
 {
     const dim3 grid((unsigned)nitems), block(512);
-    if (mt == 8) {
+    if (mt == 32) {
+        if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 1, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else if (r == 128) hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 1, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+        else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 1, MAP, false>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
+    } else if (mt == 8) {
         if (r == 64) hipLaunchKernelGGL((compress_bf16_wide_kernel<4, 4, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
         else if (r == 128) hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP, true>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
         else hipLaunchKernelGGL((compress_bf16_wide_kernel<8, 4, MAP, false>), grid, block, 0, s, mats, items, seeds, r, a, b, partials, counters);
@@ -551,7 +555,7 @@ hipError_t launch_narrow(const MatDev* mats, const WorkItem* items, int nitems, 
 
 }  // namespace
 
-// All items of one launch share one MT (rows per workgroup = 128 * MT; 8 and 16 select the wide
+// All items of one launch share one MT (rows per workgroup = 128 * MT; 8, 16 and 32 select the wide
 // kernel), chosen by the host.  partials / counters: workspace of the wide kernel's shared-column
 // mode (may be null when no item has nparts > 1).
 hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, int nitems,
@@ -562,7 +566,7 @@ hipError_t launch_compress_bf16_mt(const MatDev* mats, const WorkItem* items, in
     if (r != 64 && r != 128 && r != 256) return hipErrorInvalidValue;
     if (grad_is_f32 && mt > 4) return hipErrorInvalidValue;   // fp32 gradients: first kernel only
     if (map != 0 && map != 1) return hipErrorInvalidValue;
-    if (mt == 8 || mt == 16)     // wide kernel: 512 (8) or 256 (16) rows per workgroup, rank slices of 128 (64 at r = 64)
+    if (mt == 8 || mt == 16 || mt == 32)     // wide kernel: 512 (8), 256 (16) or 128 (32) rows per workgroup, rank slices of 128 (64 at r = 64)
         return (map == 1) ? launch_wide<1>(mats, items, nitems, seeds, r, mt, a, b, partials, counters, s)
                           : launch_wide<0>(mats, items, nitems, seeds, r, mt, a, b, partials, counters, s);
     const dim3 grid((unsigned)nitems), block(256);

@@ -163,10 +163,10 @@ def test_compress_bf16_path_fp32_gradients(n, m, r, mt):
 
 
 # every launch shape of the bf16 compress kernel, forced through the tuning hook: the narrow
-# kernel (128 / 256 / 512 rows per workgroup) and the wide one (8 / 16: 512 / 256 rows, rank slices
-# of 128),
+# kernel (128 / 256 / 512 rows per workgroup) and the wide one (8 / 16 / 32: 512 / 256 / 128 rows, rank
+# slices of 128),
 # on shapes with ragged row blocks, a ragged last column tile and odd / even tile counts
-@pytest.mark.parametrize("mt", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("mt", [1, 2, 4, 8, 16, 32])
 @pytest.mark.parametrize("n,m,r", [(700, 520, 256), (1100, 64, 128), (97, 1160, 64), (513, 200, 256)])
 def test_compress_bf16_every_launch_shape(n, m, r, mt):
     seed = 2500 + n + m + r
@@ -194,7 +194,7 @@ def test_compress_bf16_every_launch_shape(n, m, r, mt):
 # the wide kernel with the columns of a row block shared between workgroups (partial products
 # combined by the last workgroup to arrive): several parts, ragged last part, two launches in a
 # row on the same descriptor set (the arrival counters must be back at zero), grouped matrices
-@pytest.mark.parametrize("mt", [8, 16])
+@pytest.mark.parametrize("mt", [8, 16, 32])
 @pytest.mark.parametrize("kc", [64, 192, 448])
 @pytest.mark.parametrize("r", [64, 256])
 def test_compress_bf16_shared_columns(r, kc, mt):

@@ -27,7 +27,7 @@ def check_compress(shapes, r, gdt):
         rows_per_wg, slice_w, nslices, rp = 64 * mt, None, 1, max(16, r)
     else:
         wide = mt >= 8
-        rows_per_wg = 512 if mt == 8 else 256 if mt == 16 else 128 * mt
+        rows_per_wg = 512 if mt == 8 else 256 if mt == 16 else 128 if mt == 32 else 128 * mt
         slice_w = (64 if r == 64 else 128) if wide else 64
         nslices, rp = r // slice_w, slice_w
     groups = {}
