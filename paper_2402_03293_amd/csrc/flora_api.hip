@@ -303,17 +303,23 @@ void build_compress_bf16_items(Plan& p)
 // A workgroup regenerates its slice of A once and reuses it for every row it owns, so the
 // generator's work is n m r / rows: 1024 rows make it a few percent of the kernel.  More
 // would only make workgroups long and unequal (the last ones to start then run alone);
-// fewer are chosen when the launch would otherwise not fill the chip.
+// fewer are chosen when the launch would otherwise not fill the chip.  A launch over one or two
+// matrices cannot fill it whatever the rows; there the fewest workgroups per compute unit in
+// a row finish first, and rows go down (to 32 at least) until there are about 140 workgroups
+// (single matrices of GPT-2 XL and T5-3B shapes: update 27-31 -> 18-27 us at r = 256, 17-20 ->
+// 10-17 us at r = 64).
 int choose_decompress_rows(const std::vector<MatDev>& mats, int cols)
 {
     if (g_tune.decompress_rows) return g_tune.decompress_rows;
+    auto wgs = [&](int rows) {
+        long long w = 0;
+        for (const MatDev& M : mats) w += ((M.n + rows - 1) / rows) * ((M.m + cols - 1) / cols);
+        return w;
+    };
     int rows = 1024;
-    for (; rows > kDecompressRows; rows /= 2) {
-        long long wgs = 0;
-        for (const MatDev& M : mats)
-            wgs += ((M.n + rows - 1) / rows) * ((M.m + cols - 1) / cols);
-        if (wgs >= 2048) break;
-    }
+    for (; rows > kDecompressRows; rows /= 2)
+        if (wgs(rows) >= 2048) break;
+    for (; rows > 32 && wgs(rows) < 140; rows /= 2) {}
     return rows;
 }
 
@@ -1113,17 +1119,22 @@ void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int coun
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
 {
     if (!mats || count <= 0 || r <= 0) return 0;
+    std::lock_guard<std::mutex> guard(g_lock);      // reads the tuning knobs
     std::vector<MatDev> md((size_t)count);
     size_t items = 0;
     for (int l = 0; l < count; ++l) {
         MatDev M{};
         M.n = mats[l].n; M.m = mats[l].m;
         if (M.n < 1 || M.m < 1) return 0;
-        M.nrowblocks = (int)((M.n + kDecompressRows - 1) / kDecompressRows);
+        md[(size_t)l] = M;
+    }
+    // the fewest rows per workgroup either decompress kernel would choose for this set
+    const int rows = std::min(choose_decompress_rows(md, kDecompressCols), choose_decompress_rows(md, kDecompressColsVec));
+    for (MatDev& M : md) {
+        M.nrowblocks = (int)((M.n + rows - 1) / rows);
         M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
         M.nitems = M.nrowblocks * M.ncolchunks;
         items += (size_t)M.nitems;
-        md[(size_t)l] = M;
     }
     size_t transfer = 0;
     for (const MatDev& M : md) {
