@@ -213,9 +213,24 @@ void build_compress_bf16_items(Plan& p)
         const long long kc_opt[3] = {0, 1536, 768};
         mt = 16; kc = 768;
         bool found = false;
+        // An option also has to be balanced: a workgroup sweeps its columns 64 at a time, and when
+        // the longest sweep is more than one and a half times a compute unit's even share of all
+        // tiles, that workgroup finishes long after the rest (24 matrices of T5-3B shapes with whole
+        // rows: 384 workgroups, the 16384-column ones 256 tiles long against an even share of 48,
+        // 574 us; in parts of 1536 columns 210 us).
+        auto balanced = [&](int rows, long long kc) {
+            long long total = 0, longest = 0;
+            for (int l = 0; l < p.count; ++l) {
+                const long long m = p.host_mats[l].m;
+                const long long tiles = (m + 63) / 64;
+                total += (p.host_mats[l].n + rows - 1) / rows * (p.r / wide_slice) * tiles;
+                longest = std::max(longest, kc > 0 ? std::min(tiles, (kc + 63) / 64) : tiles);
+            }
+            return 2 * longest <= 3 * std::max<long long>(1, total / 256);
+        };
         for (int ri = 0; ri < 2 && !found; ++ri)
             for (int ki = 0; ki < 3 && !found; ++ki)
-                if (wide_wgs(rows_opt[ri], kc_opt[ki]) >= 384) {
+                if (wide_wgs(rows_opt[ri], kc_opt[ki]) >= 384 && (kc_opt[ki] > 0 || balanced(rows_opt[ri], 0))) {
                     mt = rows_opt[ri] == 512 ? 8 : 16;
                     kc = kc_opt[ki];
                     found = true;
@@ -303,12 +318,16 @@ void build_compress_bf16_items(Plan& p)
 // A workgroup regenerates its slice of A once and reuses it for every row it owns, so the
 // generator's work is n m r / rows: 1024 rows make it a few percent of the kernel.  More
 // would only make workgroups long and unequal (the last ones to start then run alone);
-// fewer are chosen when the launch would otherwise not fill the chip.  A launch over one or two
-// matrices cannot fill it whatever the rows; there the fewest workgroups per compute unit in
-// a row finish first, and rows go down (to 32 at least) until there are about 140 workgroups
-// (single matrices of GPT-2 XL and T5-3B shapes: update 27-31 -> 18-27 us at r = 256, 17-20 ->
+// fewer are chosen when the launch would otherwise not fill the chip: at ranks up to 64, where
+// the pass is bound by the weights' traffic, until there are 2048 workgroups (but not below
+// 256 rows); at r = 256, where regenerating A is a large part of a workgroup's time, 140 are
+// enough, and at r = 128 about 1000 (launches over the matrices of one to eight transformer
+// blocks of GPT-2 XL and T5-3B shapes, r = 256: update 84-453 -> 63-407 us).  A launch over one
+// or two matrices cannot fill the chip whatever the rows; there the fewest workgroups per
+// compute unit in a row finish first, and rows go down (to 32 at least) until there are about
+// 140 workgroups (single matrices of those shapes: update 27-31 -> 18-27 us at r = 256, 17-20 ->
 // 10-17 us at r = 64).
-int choose_decompress_rows(const std::vector<MatDev>& mats, int cols)
+int choose_decompress_rows(const std::vector<MatDev>& mats, int cols, int r)
 {
     if (g_tune.decompress_rows) return g_tune.decompress_rows;
     auto wgs = [&](int rows) {
@@ -316,9 +335,10 @@ int choose_decompress_rows(const std::vector<MatDev>& mats, int cols)
         for (const MatDev& M : mats) w += ((M.n + rows - 1) / rows) * ((M.m + cols - 1) / cols);
         return w;
     };
+    const long long enough = r >= 256 ? 140 : (r >= 128 ? 1000 : 2048);
     int rows = 1024;
     for (; rows > kDecompressRows; rows /= 2)
-        if (wgs(rows) >= 2048) break;
+        if (wgs(rows) >= enough) break;
     for (; rows > 32 && wgs(rows) < 140; rows /= 2) {}
     return rows;
 }
@@ -332,7 +352,7 @@ void build_decompress_items(Plan& p)
     p.vec = vec;
     const int cols = vec ? kDecompressColsVec : kDecompressCols;
     // (the vector kernel addresses a workgroup's state rows with 32-bit byte offsets)
-    const int rows_per_wg = std::min(choose_decompress_rows(p.host_mats, cols), vec ? (1 << 20) : 0x7fffffe0);
+    const int rows_per_wg = std::min(choose_decompress_rows(p.host_mats, cols, p.r), vec ? (1 << 20) : 0x7fffffe0);
     struct Group { int mat, rb, row0, rows, nchunks; };
     std::vector<Group> groups;
     for (int l = 0; l < p.count; ++l) {
@@ -1129,7 +1149,7 @@ size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
         md[(size_t)l] = M;
     }
     // the fewest rows per workgroup either decompress kernel would choose for this set
-    const int rows = std::min(choose_decompress_rows(md, kDecompressCols), choose_decompress_rows(md, kDecompressColsVec));
+    const int rows = std::min(choose_decompress_rows(md, kDecompressCols, r), choose_decompress_rows(md, kDecompressColsVec, r));
     for (MatDev& M : md) {
         M.nrowblocks = (int)((M.n + rows - 1) / rows);
         M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
