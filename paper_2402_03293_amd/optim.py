@@ -17,6 +17,10 @@ Schedules follow the paper's two algorithms:
   into the momentum, b = (1 - beta) / tau, which by linearity is Algorithm 2 on the mean
   gradient of the cycle.
 
+``state_dict()`` / ``load_state_dict()`` carry the compressed states together with the seeds and
+counters that stand for the projections (the paper's point that only the seed is kept), so a resumed
+run continues bit for bit.
+
 Only 2-D parameters, fp32 or bf16, are accepted (the paper projects the attention and feed-forward
 weight matrices).  Gradients may be fp32 or bf16 at every rank; at ranks 64/128/256 bf16 gradients take
 the fastest kernel (``param.grad_dtype = torch.bfloat16`` makes autograd produce them).
@@ -200,3 +204,42 @@ class Flora:
         for h in self._handles:
             h.remove()
         self._handles = []
+
+    # ------------------------------------------------------------------ checkpoints
+    def state_dict(self):
+        """Everything a resumed run needs: the compressed states, the second-moment statistics and,
+        because the projections are never stored, the seeds and counters that define them."""
+        def clone(xs):
+            return None if xs is None else [x.detach().clone() for x in xs]
+        return {
+            "config": {"r": self.r, "tau": self.tau, "beta": self.beta, "kappa": self.kappa, "rule": self.rule,
+                       "seed": self.global_seed, "shapes": [tuple(s) for s in self.shapes]},
+            "state": clone(self.state), "row_stat": clone(self.row_stat), "col_stat": clone(self.col_stat),
+            "second": clone(self.second),
+            "sumsq": None if self.sumsq is None else self._sumsq_buf.detach().clone(),
+            "micro": list(self.micro), "updates": list(self.updates), "epoch": list(self.epoch),
+            "matrix_seed": [int(x) for x in self.seed], "sumsq_ready": self._sumsq_ready,
+        }
+
+    def load_state_dict(self, sd):
+        cfg = sd["config"]
+        mine = {"r": self.r, "tau": self.tau, "beta": self.beta, "kappa": self.kappa, "rule": self.rule,
+                "seed": self.global_seed, "shapes": [tuple(s) for s in self.shapes]}
+        if {k: (list(map(tuple, v)) if k == "shapes" else v) for k, v in cfg.items()} != mine:
+            raise ValueError("checkpoint was written by an optimizer with a different configuration")
+
+        def put(dst, src):
+            if (dst is None) != (src is None):
+                raise ValueError("checkpoint does not match the update rule")
+            if dst is not None:
+                for d, x in zip(dst, src):
+                    d.copy_(x)
+        put(self.state, sd["state"])
+        put(self.row_stat, sd["row_stat"])
+        put(self.col_stat, sd["col_stat"])
+        put(self.second, sd["second"])
+        if self.sumsq is not None:
+            self._sumsq_buf.copy_(sd["sumsq"])
+        self.micro, self.updates, self.epoch = list(sd["micro"]), list(sd["updates"]), list(sd["epoch"])
+        self.seed = [int(x) for x in sd["matrix_seed"]]
+        self._sumsq_ready = bool(sd["sumsq_ready"])

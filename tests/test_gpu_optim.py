@@ -184,3 +184,37 @@ def test_bf16_parameters_layer_by_layer():
         assert params[l].dtype == torch.bfloat16
         assert rel_fro(to64(opt.state[l]), ref.M[l]) < 2e-2
         assert rel_fro(to64(params[l]), W[l]) < 2e-2
+
+
+@pytest.mark.parametrize("rule,tau,beta", [("sgd", 1, 0.9), ("adafactor", 2, 0.0), ("unfactored", 2, 0.9)])
+def test_checkpoint_and_resume_reproduce_the_uninterrupted_run(rule, tau, beta):
+    """The projections exist only as seeds and counters: a resumed optimizer must pick up the same
+    ones.  Five calls straight through against three calls, state_dict, a new optimizer, two more."""
+    r, kappa, steps, cut = 16, 2, 6, 3
+    grads = make_grads(steps, 91, False)
+
+    def run(resume):
+        params = make_params(5, False)
+        kw = dict(lr=None if rule != "sgd" else 0.05, tau=tau, beta=beta, kappa=kappa, rule=rule, seed=21)
+        opt = optim.Flora(params, r, **kw)
+        for t in range(steps):
+            if resume and t == cut:
+                sd = opt.state_dict()
+                weights = [p.detach().clone() for p in params]
+                params = [torch.nn.Parameter(w) for w in weights]
+                opt = optim.Flora(params, r, **kw)
+                opt.load_state_dict(sd)
+            backward_with(params, grads[t])
+            opt.step()
+            opt.zero_grad()
+        torch.cuda.synchronize()
+        return [p.detach().clone() for p in params], [s.clone() for s in opt.state]
+
+    W_a, S_a = run(False)
+    W_b, S_b = run(True)
+    for x, y in zip(W_a + S_a, W_b + S_b):
+        assert torch.equal(x, y)
+    other = optim.Flora(make_params(5, False), r, lr=0.05, tau=tau + 1, beta=beta, kappa=kappa, rule="sgd", seed=21)
+    with pytest.raises(ValueError):
+        other.load_state_dict(optim.Flora(make_params(5, False), r, lr=0.05, tau=tau, beta=beta, kappa=kappa,
+                                          rule="sgd", seed=21).state_dict())
