@@ -159,7 +159,7 @@ def compress(G, r: int, seed: int, state=None, a: float = 1.0, b: float = 1.0,
 
 
 def compress_mapped(G, r: int, seed: int, input_map: str, state=None, a: float = 1.0, b: float = 1.0) -> np.ndarray:
-    """Compressed EMA of another statistic (closing remark of Section 2.3): the compression line with
+    """Compressed EMA of another statistic (closing remark of Section 2.4, "Sublinear memory momentum"): the compression line with
     phi(G) in place of G, phi elementwise; "square" gives the second moment's term G * G."""
     G = _f64c(G)
     if input_map == "identity":

@@ -43,7 +43,7 @@ def _hipcc() -> str:
 
 def _compile(src: str, force: bool) -> Path:
     obj = OBJ / (src + ".o")
-    deps = [CSRC / src] + list(CSRC.glob("*.h")) + [HERE.parent / "include" / "flora.h"]
+    deps = [CSRC / src] + list(CSRC.glob("*.h")) + list((HERE.parent / "include").glob("*.h"))
     if not force and obj.exists() and all(obj.stat().st_mtime >= d.stat().st_mtime for d in deps):
         return obj
     cmd = [_hipcc(), *HIPCC_FLAGS, "-c", str(CSRC / src), "-o", str(obj)]

@@ -4,6 +4,7 @@
 // entry point.  No arithmetic of the method happens here; it all runs in the
 // gfx950 kernels.
 #include "../../include/flora.h"
+#include "../../include/flora_debug.h"
 #include "flora_gen.hip.h"
 #include "flora_internal.h"
 

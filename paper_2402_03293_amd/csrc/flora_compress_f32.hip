@@ -4,7 +4,7 @@
 // a = beta, b = 1 - beta).  G is fp32 or bf16 and is used exactly; products and
 // sums are fp32 (v_mfma_f32_16x16x4_f32).  With MAP = 1 the input is the elementwise
 // square of G, taken in fp32 on the operand registers (the compressed EMA of another
-// statistic that Section 2.3 closes with: here the second moment).
+// statistic that the "Sublinear memory momentum" paragraph of Section 2.4 closes with: here the second moment).
 //
 // One workgroup owns 64 * MT rows of one matrix and sweeps all m columns in
 // tiles of 64.  Its 4 * KG waves form KG column groups of 4 waves; group kg

@@ -68,15 +68,9 @@ __device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float neg2_
 {
     const float u1 = uniform23(xa);
     const float u2 = uniform23(xb);
-#if defined(FLORA_GEN_LIBM)
-    const float rho = sqrtf(logf(u1) * (neg2_ln2_over_r * 1.4426950408889634f));
-    float s, c;
-    sincospif(2.0f * u2, &s, &c);
-#else
     const float rho = __builtin_amdgcn_sqrtf(__builtin_amdgcn_logf(u1) * neg2_ln2_over_r);
     const float s = __builtin_amdgcn_sinf(u2);
     const float c = __builtin_amdgcn_cosf(u2);
-#endif
     z_cos = rho * c;
     z_sin = rho * s;
 }

@@ -598,7 +598,7 @@ def test_projection_entries_match_the_stored_fixture():
             assert list(A[row, :8]) == got
 
 
-# ---- compressed EMA of another statistic (closing remark of Section 2.3): the second moment
+# ---- compressed EMA of another statistic (closing remark of Section 2.4, "Sublinear memory momentum"): the second moment
 
 def test_mapped_compress_is_the_matrix_product_of_the_squares():
     rng = np.random.default_rng(61)
