@@ -16,13 +16,10 @@ from paper_2402_03293_amd import flora  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
-TOL_F32 = 1e-5
-TOL_BF16 = 2e-2
+from parity_bars import TOL_BF16, TOL_F32, tol_for, update_bar  # noqa: E402,F401
 DEV = "cuda:0"
 
 
-def tol_for(r):
-    return TOL_F32 if r <= 32 else TOL_BF16
 
 
 def to64(t):
@@ -91,7 +88,7 @@ def test_apply_update_unfactored(n, m, r, clip_d, beta2, scaled):
     Wr, Vr = oracle.adafactor_step(to64(W0), Gt, V=to64(V0), beta2=beta2, eps1=eps1, eps2=eps2, clip_d=clip_d,
                                    step=step, scale_parameter=scaled)
     tol = tol_for(r)
-    assert rel_fro(to64(V), Vr) < 2 * tol
+    assert rel_fro(to64(V), Vr) < tol
     dg, do = to64(W) - to64(W0), Wr - to64(W0)
     if beta2 == 0.0:
         # V = Gt^2 makes U = sign(Gt): where |Gt| is within rounding of zero the sign is not
@@ -100,10 +97,10 @@ def test_apply_update_unfactored(n, m, r, clip_d, beta2, scaled):
         assert keep.mean() > 0.9
         assert np.abs(dg[~keep]).max() <= 1.001 * np.abs(do).max()
         dg, do = dg[keep], do[keep]
-    assert rel_fro(dg, do) < max(2 * tol, 5e-5)
+    assert rel_fro(dg, do) < update_bar(r, Wr, to64(W0))
     # the sum of squares left behind is that of the new weights
     assert float(ss[0]) == pytest.approx(float((to64(W) ** 2).sum()), rel=5e-6)
-    assert float(ss[0]) == pytest.approx(float((Wr ** 2).sum()), rel=max(tol, 1e-4))
+    assert float(ss[0]) == pytest.approx(float((Wr ** 2).sum()), rel=tol)
 
 
 def test_unfactored_first_step_is_sign_descent_on_the_gpu():
@@ -174,9 +171,18 @@ def test_adafactor_steps_with_schedules_and_carried_parameter_scale(r, rule):
             tol = tol_for(r)
             # this step's movement on either side (the two trajectories stay within the bar of
             # each other, so second moments and parameter scales agree to the same order)
-            assert rel_fro(to64(W[l]) - prev[l], Wo[l] - before) < max(3 * tol, 1e-4), (t, l)
-            assert rel_fro(to64(W[l]), Wo[l]) < max(tol, 1e-4), (t, l)
-            assert float(ss[l, 0]) == pytest.approx(float((Wo[l] ** 2).sum()), rel=1e-3), (t, l)
+            dg, do = to64(W[l]) - prev[l], Wo[l] - before
+            if rule == "unfactored" and obeta2 == 0.0:
+                # the schedule's first step has beta2 = 0: V = Gt^2 and U = sign(Gt), whose value
+                # where |Gt| is within rounding of zero no tolerance can pin (see the single-step
+                # test above): those entries are held to the size of a step, the rest to the bar
+                keep = np.abs(Gt) > (0.05 if r > 32 else 1e-3) * np.sqrt((Gt ** 2).mean())
+                assert keep.mean() > 0.9
+                assert np.abs(dg[~keep]).max() <= 1.001 * np.abs(do).max()
+                dg, do = dg[keep], do[keep]
+            assert rel_fro(dg, do) < update_bar(r, Wo[l], before), (t, l)
+            assert rel_fro(to64(W[l]), Wo[l]) < (1e-6 if r <= 32 else tol), (t, l)
+            assert float(ss[l, 0]) == pytest.approx(float((Wo[l] ** 2).sum()), rel=tol), (t, l)
         assert float(max(s.abs().max() for s in St)) == 0.0
 
 
@@ -213,17 +219,17 @@ def test_bf16_kernels_unfactored_and_scaled_factored(n, m, r, rows, vec):
     Gt = oracle.decompress(to64(S), m, seed, alpha=alpha)
     Wr, Vr = oracle.adafactor_step(to64(W0), Gt, V=to64(V0), beta2=beta2, eps1=eps1, eps2=eps2, clip_d=clip_d,
                                    step=step)
-    assert rel_fro(to64(V), Vr) < 2 * TOL_BF16
+    assert rel_fro(to64(V), Vr) < TOL_BF16
     # row by row: a misplaced tile would hide in the norm of the whole
     dV = to64(V) - Vr
-    assert (np.linalg.norm(dV, axis=1) / np.linalg.norm(Vr, axis=1)).max() < 2 * TOL_BF16
-    assert rel_fro(to64(Wu) - to64(W0), Wr - to64(W0)) < 2 * TOL_BF16
+    assert (np.linalg.norm(dV, axis=1) / np.linalg.norm(Vr, axis=1)).max() < TOL_BF16
+    assert rel_fro(to64(Wu) - to64(W0), Wr - to64(W0)) < TOL_BF16
     assert float(ssu[0]) == pytest.approx(float((to64(Wu) ** 2).sum()), rel=5e-6)
     Wr, Rr, Kr = oracle.adafactor_step(to64(W0), Gt, R=to64(R0), K=to64(K0), beta2=beta2, eps1=eps1, eps2=eps2,
                                        clip_d=clip_d, step=step)
-    assert rel_fro(to64(R), Rr) < 2 * TOL_BF16
-    assert rel_fro(to64(K), Kr) < 2 * TOL_BF16
-    assert rel_fro(to64(Wf) - to64(W0), Wr - to64(W0)) < 2 * TOL_BF16
+    assert rel_fro(to64(R), Rr) < TOL_BF16
+    assert rel_fro(to64(K), Kr) < TOL_BF16
+    assert rel_fro(to64(Wf) - to64(W0), Wr - to64(W0)) < TOL_BF16
     assert float(ssf[0]) == pytest.approx(float((to64(Wf) ** 2).sum()), rel=5e-6)
 
 
@@ -312,7 +318,7 @@ def test_updates_on_bf16_weights(n, m, r, rule):
         flora.weight_sumsq(mats, flora.BF16)
         flora.apply_update(mats, r, flora.BF16, flora.unfactored_update(lr, alpha, 0.8, 1e-30, 1.0, scale_parameter=True))
         Wr, Vr = oracle.adafactor_step(W064, Gt, V=to64(V0), beta2=0.8, step=lr)
-        assert rel_fro(to64(V), Vr) < 2 * tol_for(r)
+        assert rel_fro(to64(V), Vr) < tol_for(r)
     sync()
     assert W.dtype == torch.bfloat16
     got, want = to64(W), bf16_round(Wr)

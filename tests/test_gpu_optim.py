@@ -10,6 +10,7 @@ import oracle
 
 torch = pytest.importorskip("torch")
 from paper_2402_03293_amd import flora, optim  # noqa: E402
+from parity_bars import update_bar  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -78,7 +79,7 @@ def test_momentum_sgd_with_resampling(r, bf16, layerwise):
     tol = 1e-5 if r <= 32 else 2e-2
     for l in range(len(SHAPES)):
         assert rel_fro(to64(opt.state[l]), ref.M[l]) < tol
-        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < max(tol, 3e-5)
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < update_bar(r, W[l], W0[l])
         assert opt.seed[l] == ref.seed[l] and opt.updates[l] == steps
 
 
@@ -109,7 +110,7 @@ def test_accumulation_cycles(rule, layerwise):
             fac["step"], fac["beta2"] = oracle.adafactor_schedule(c + 1)
             W, _, _ = oracle.algorithm1_cycle(W, gsteps, r, gseed, c, 0.0, rule="adafactor", factored=fac)
     for l in range(len(SHAPES)):
-        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < 1e-4
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < update_bar(r, W[l], W0[l])
         assert opt.updates[l] == cycles and opt.epoch[l] == cycles
 
 
@@ -140,8 +141,8 @@ def test_micro_batches_into_momentum_and_unfactored_rule():
                                                step=0.01, scale_parameter=False)
     for l in range(len(SHAPES)):
         assert rel_fro(to64(opt.state[l]), ref.M[l]) < 1e-5
-        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < 1e-4
-        assert rel_fro(to64(opt.second[l]), V[l]) < 1e-4
+        assert rel_fro(to64(params[l]) - W0[l], W[l] - W0[l]) < update_bar(r, W[l], W0[l])
+        assert rel_fro(to64(opt.second[l]), V[l]) < 1e-5
 
 
 def test_front_end_rejects_what_the_library_cannot_take():

@@ -8,6 +8,7 @@ import oracle
 
 torch = pytest.importorskip("torch")
 from paper_2402_03293_amd import flora  # noqa: E402
+from parity_bars import update_bar  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -66,6 +67,6 @@ def test_random_shape_sets(case):
         assert rel_fro(to64(out[l]), Gt) < tol, ("decompress", shapes[l], r)
         assert not torch.isnan(out[l]).any()
         assert torch.equal(Sd[l], S0[l])
-        assert rel_fro(to64(W[l]) - to64(W0[l]), -lr * Gt) < max(tol, 3e-5), ("update", shapes[l], r)
+        assert rel_fro(to64(W[l]) - to64(W0[l]), -lr * Gt) < update_bar(r, to64(W0[l]) - lr * Gt, to64(W0[l])), ("update", shapes[l], r)
         Tr = oracle.transfer(to64(S0[l]), m, seeds[l], seeds2[l])
-        assert rel_fro(to64(St[l]), Tr) < 2e-5, ("transfer", shapes[l], r)
+        assert rel_fro(to64(St[l]), Tr) < 1e-5, ("transfer", shapes[l], r)      # fp32 at every rank

@@ -104,8 +104,11 @@ def test_contrast_through_the_library(r, bf16):
         # and the oracle's own trajectories (fp64 gradients of its own weights) end in the same place
         ref_rp = run_oracle(Ws, r, eta, steps, False, gseed)
         ref_rrp = run_oracle(Ws, r, eta, steps, True, gseed)
-        assert np.linalg.norm(out[False] - ref_rp) / np.linalg.norm(ref_rp) < 10 * tol
-        assert np.linalg.norm(out[True] - ref_rrp) / np.linalg.norm(ref_rrp) < 10 * tol
+        e_rp = np.linalg.norm(out[False] - ref_rp) / np.linalg.norm(ref_rp)
+        e_rrp = np.linalg.norm(out[True] - ref_rrp) / np.linalg.norm(ref_rrp)
+        print("pilot contrast through the library: trajectory ends %.2e (fixed), %.2e (resampled) from the oracle's"
+              % (e_rp, e_rrp))
+        assert e_rp < tol and e_rrp < tol
     else:
         # bf16 gradients are rounded each step, which the fp64 trajectory does not model: compare
         # with the closed-form limit of the fixed projection instead (reached to rounding level)
