@@ -35,21 +35,30 @@
  *     bf16 on the fly; bf16 gradients are used exactly and take the fastest
  *     kernel, fp32 gradients are rounded to bf16, nearest even, in registers).
  *     Other r: FLORA_ERR_UNSUPPORTED.
- *   - The library keeps private device memory per (set of matrix shapes, stream):
- *     the work tables of the grouped launches, the r x r transfer matrices,
- *     statistic partials, for small launches the partial products and arrival
- *     counters of row blocks whose columns are shared between workgroups, and
- *     device copies of descriptor tables.  It is allocated with hipMalloc the
- *     first time a set of shapes is seen on a stream and reused afterwards;
- *     flora_shutdown() releases it.  A call whose pointers have been seen
- *     before uploads nothing; one with new pointers (another buffer of a ring,
- *     a freshly allocated gradient) costs one small asynchronous copy and no
- *     allocation or synchronisation, so calling once per matrix from a
- *     training loop stays cheap.  A call whose shapes and pointers have been
- *     seen on its stream is kernel launches only, so it may be recorded into a
- *     HIP graph (seeds are kernel arguments: a resample means a new capture or
- *     a node update).  No per-matrix state (seed, step, epoch) is kept between
- *     calls: that lives with the caller.
+ *   - Device memory beyond the caller's tensors ("workspace").  Per (set of matrix shapes,
+ *     stream) the library needs the work tables of the grouped launches, the r x r transfer
+ *     matrices, statistic partials, for small launches the partial products and arrival counters
+ *     of row blocks whose columns are shared between workgroups, and device copies of descriptor
+ *     tables.  By default it allocates this with hipMalloc (and pinned staging with
+ *     hipHostMalloc) the first time a set of shapes is seen on a stream and reuses it afterwards;
+ *     flora_shutdown() releases it.  A caller that wants to place and count that memory itself
+ *     hands the library a buffer with flora_set_workspace(): from then on everything above is
+ *     carved from the caller's buffer and the library calls neither hipMalloc nor hipHostMalloc.
+ *     Either way a call whose pointers have been seen before uploads nothing; one with new
+ *     pointers (another buffer of a ring, a freshly allocated gradient) costs one small
+ *     asynchronous copy and no allocation or synchronisation, so calling once per matrix from a
+ *     training loop stays cheap.  No per-matrix state (seed, step, epoch) is kept between calls:
+ *     that lives with the caller.
+ *   - HIP graphs.  A call whose shapes and pointers have been seen on its stream is kernel
+ *     launches only and may be recorded into a HIP graph (seeds are kernel arguments: a resample
+ *     means a new capture or a node update).  The captured kernels read the library's cached
+ *     tables and descriptor images, so these must stay where they are for as long as the graph is
+ *     replayed: between capture and the last replay do not call flora_set_tuning,
+ *     flora_set_workspace or flora_shutdown, do not let calls with other pointer sets on the same
+ *     shapes push the captured image out (the library keeps the 16 most recently used images
+ *     per plan for sets of more than 32 matrices, 64 for sets of 5 to 32, 512 for smaller ones;
+ *     8 with a caller-owned workspace), and stay below 1024 distinct (shape set, stream, entry
+ *     point) combinations.
  *   - Calls on one stream execute in order.  Calls issued concurrently from
  *     several host threads are serialised by an internal lock.  Two calls on
  *     the same matrices (the same grad / weight / state pointers) must not
@@ -225,9 +234,30 @@ uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t ep
 void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int count, uint64_t epoch,
                         uint64_t* seeds_out);
 
-/* Upper bound on the bytes of private workspace the library would hold for this set of
- * matrices. */
+/* Caller-owned workspace (Section 2.4, "Memory analysis": the method's point is what a training
+ * step keeps in memory, so the library's own footprint is the caller's to place and count).
+ *
+ * flora_workspace_bytes: the smallest workspace with which every entry point accepts this set of
+ * matrices at rank r, i.e. what the most demanding call occupies: flora_fused_step with a
+ * transfer and an Adafactor rule (its transfer, compress and update plans are resident together).
+ * Exact, not a bound: with one 256-byte unit less that call returns FLORA_ERR_INVALID.  Only n and
+ * m of the descriptors are read.  Host only.  0 for an invalid set or rank.
+ *
+ * flora_set_workspace: dev_ptr is DEVICE memory, 256-byte aligned, of `bytes` bytes, owned by the
+ * caller and kept alive until the workspace is replaced, cleared (dev_ptr NULL and bytes 0:
+ * back to library-allocated memory) or flora_shutdown().  While it is set the library calls no
+ * hipMalloc / hipHostMalloc: tables, transfer matrices, partials, counters and descriptor images
+ * of every call come out of this buffer, and uploads come from pageable host memory.  A call
+ * whose plans do not fit is refused with FLORA_ERR_INVALID before anything is enqueued.  When
+ * the plans of a call fit but not beside those of earlier calls, the earlier ones are dropped
+ * and the buffer is refilled (a step that alternates between calls then re-uploads its tables:
+ * give the workspace the sum of what its calls need to avoid that; flora_workspace_bytes is
+ * enough for one fused step).  Calls that use the workspace must be ordered by the caller (one
+ * stream, or events between streams): the refill relies on it.  Results are bit for bit those
+ * of the library-allocated mode.  Drops every cached plan.  Not to be called while kernels of
+ * earlier calls may still run, or between a graph capture and its replays. */
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r);
+int flora_set_workspace(void* dev_ptr, size_t bytes);
 
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int flora_last_device_error(void);

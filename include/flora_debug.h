@@ -27,6 +27,13 @@ extern "C" {
 int64_t flora_debug_work_items(int kind, const flora_matrix_t* mats, int count, int r,
                                flora_dtype_t grad_dtype, int64_t* out, int64_t cap, int64_t* info);
 
+/* Test hook, host only: the bytes of a caller-owned workspace (flora_set_workspace) that one
+ * plan of the library occupies for this set of shapes (count <= 448): plan_kind 0 flora_compress,
+ * 1 flora_decompress / SGD update, 2 the transfer, 3 the Adafactor updates, 4 flora_weight_sumsq.
+ * = tables + work area + 8 descriptor images, each rounded up to 256 bytes.  Negative
+ * flora_status_t on bad arguments. */
+int64_t flora_debug_plan_bytes(int plan_kind, const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype);
+
 /* Measurement hook: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 16;
  * both DEVICE pointers 16-byte aligned, not overlapping).  Profiler byte counters for the
  * hot-path kernels are scaled by what they read for this copy of known size. */

@@ -98,7 +98,30 @@ struct Plan {
     std::unordered_multimap<uint64_t, int> index;   // image hash -> slot
     const MatDev* cur_mats = nullptr;   // the image of the current call
     uint64_t tick = 0;
+    // device side: a plan exists on the host first (tables and sizes) and is then placed, either in
+    // memory the library allocates or in the caller's workspace
+    bool placed = false;
+    bool in_arena = false;
+    size_t off2 = 0;                    // offset of items2 within the tables
+    size_t tbytes = 0;                  // bytes of the tables
+    size_t wbytes = 0;                  // bytes of the work area
+    bool pending = false;               // needed by the call being prepared (caller's workspace)
 };
+
+// Caller-owned workspace (flora_set_workspace).  While one is set every device buffer of a plan
+// -- tables, work area, descriptor images -- is carved from it with a bump allocator, uploads
+// come from pageable host memory (the copy call returns once the source has been staged) and
+// the library calls no hipMalloc / hipHostMalloc.  When the plans a call needs do not fit
+// beside those already placed, all placed plans are dropped and the workspace is refilled: the
+// caller keeps the calls that use it ordered (one stream, or events), so kernels of earlier calls
+// have consumed their tables before the refill's copies land.
+struct Arena {
+    char* base = nullptr;
+    size_t size = 0;
+    size_t used = 0;
+};
+Arena g_ws;
+constexpr int kArenaImages = 8;         // descriptor images per plan in the caller's workspace
 
 // Launch-shape knobs, settable through flora_set_tuning (0 = let the library choose).
 struct Tuning {
@@ -122,13 +145,21 @@ void free_plan(Plan* p)
         if (im.ev_pending) (void)hipEventSynchronize(im.ev);
         if (im.ev) (void)hipEventDestroy(im.ev);
     }
-    // hipFree waits for the device, so kernels still reading these buffers have finished
-    if (p->d_tables) (void)hipFree(p->d_tables);
-    if (p->d_work) (void)hipFree(p->d_work);
-    for (void* d : p->dev_slabs) (void)hipFree(d);
-    for (void* h : p->pin_slabs) (void)hipHostFree(h);
-    if (p->h_tables) (void)hipHostFree(p->h_tables);
+    if (!p->in_arena) {
+        // hipFree waits for the device, so kernels still reading these buffers have finished
+        if (p->d_tables) (void)hipFree(p->d_tables);
+        if (p->d_work) (void)hipFree(p->d_work);
+        for (void* d : p->dev_slabs) (void)hipFree(d);
+        for (void* h : p->pin_slabs) (void)hipHostFree(h);
+        if (p->h_tables) (void)hipHostFree(p->h_tables);
+    }
     delete p;
+}
+
+// Bytes of the caller's workspace a plan occupies once placed there.
+size_t arena_need(const Plan& p)
+{
+    return round_up(p.tbytes, 256) + round_up(p.wbytes, 256) + (size_t)kArenaImages * p.mats_bytes;
 }
 
 // Work tables -----------------------------------------------------------------
@@ -485,7 +516,9 @@ bool same_shapes(const Plan& p, const std::vector<MatDev>& mats)
     return true;
 }
 
-int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
+// Host part of a plan: work tables, launch shape and the sizes of its device buffers.  Pure host
+// work, nothing is allocated on or sent to the device.
+void build_host_plan(Plan* p, const std::vector<MatDev>& mats)
 {
     const int kind = p->kind, r = p->r, count = p->count;
     p->host_mats = mats;
@@ -503,45 +536,94 @@ int create_plan(Plan* p, const std::vector<MatDev>& mats, hipStream_t stream)
     } else if (kind != kKindSumsq) {
         build_decompress_items(*p);
     }
-    const size_t off2 = round_up(sizeof(WorkItem) * p->items.size(), 256);
-    const size_t tbytes = off2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
-    if (tbytes > 0) {
-        FLORA_HIP(hipMalloc(&p->d_tables, tbytes));
-        FLORA_HIP(hipHostMalloc(&p->h_tables, tbytes, hipHostMallocDefault));
-        char* hp = static_cast<char*>(p->h_tables);
-        if (!p->items.empty()) std::memcpy(hp, p->items.data(), sizeof(WorkItem) * p->items.size());
-        if (!p->items2.empty()) std::memcpy(hp + off2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
-        // (the plan is only ever used on this stream, so everything after this copy sees it)
-        FLORA_HIP(hipMemcpyAsync(p->d_tables, p->h_tables, tbytes, hipMemcpyHostToDevice, stream));
-        p->d_items = static_cast<const WorkItem*>(p->d_tables);
-        p->d_items2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_tables) + off2);
-    }
-    size_t wbytes = workspace_bytes_for(p->host_mats, kind, r);
-    if (kind == kKindCompress) wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
-    if (wbytes > 0) {
-        FLORA_HIP(hipMalloc(&p->d_work, wbytes));
-        p->work_cap = wbytes;
-        // arrival counters start at zero (the kernel leaves them at zero again)
-        if (kind == kKindCompress && p->ws_counters > 0)
-            FLORA_HIP(hipMemsetAsync(static_cast<char*>(p->d_work) + round_up(p->ws_floats * 4, 256), 0,
-                                     p->ws_counters * 4, stream));
-    }
+    p->off2 = round_up(sizeof(WorkItem) * p->items.size(), 256);
+    p->tbytes = p->off2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
+    p->wbytes = workspace_bytes_for(p->host_mats, kind, r);
+    if (kind == kKindCompress) p->wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
     p->mats_bytes = round_up(sizeof(MatDev) * (size_t)count, 256);
     // descriptor images kept per plan: many for calls on a few matrices (a training loop that
     // steps one layer per call cycles through hundreds of pointer sets), a few for large sets
     p->image_cap = count <= 4 ? 512 : (count <= 32 ? 64 : 16);
     p->images_per_slab = (int)std::max<size_t>(1, std::min<size_t>(64, (64 * 1024) / p->mats_bytes));
+}
+
+// Device part: tables uploaded, work area ready.  In library-allocated memory, or (in_arena) at
+// the next free bytes of the caller's workspace, whose capacity the caller of this function
+// has already checked.
+int place_plan(Plan* p, hipStream_t stream)
+{
+    const size_t off2 = p->off2, tbytes = p->tbytes, wbytes = p->wbytes;
+    if (p->in_arena) {
+        p->image_cap = kArenaImages;
+        p->images_per_slab = kArenaImages;
+    }
+    auto arena_take = [&](size_t bytes) {
+        char* q = g_ws.base + g_ws.used;
+        g_ws.used += round_up(bytes, 256);
+        return static_cast<void*>(q);
+    };
+    if (tbytes > 0) {
+        if (p->in_arena) {
+            p->d_tables = arena_take(tbytes);
+            // pageable source: the copy call returns once the source has been staged
+            static thread_local std::vector<char> stage;
+            stage.assign(tbytes, 0);
+            if (!p->items.empty()) std::memcpy(stage.data(), p->items.data(), sizeof(WorkItem) * p->items.size());
+            if (!p->items2.empty()) std::memcpy(stage.data() + off2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
+            FLORA_HIP(hipMemcpyAsync(p->d_tables, stage.data(), tbytes, hipMemcpyHostToDevice, stream));
+        } else {
+            FLORA_HIP(hipMalloc(&p->d_tables, tbytes));
+            FLORA_HIP(hipHostMalloc(&p->h_tables, tbytes, hipHostMallocDefault));
+            char* hp = static_cast<char*>(p->h_tables);
+            if (!p->items.empty()) std::memcpy(hp, p->items.data(), sizeof(WorkItem) * p->items.size());
+            if (!p->items2.empty()) std::memcpy(hp + off2, p->items2.data(), sizeof(WorkItem) * p->items2.size());
+            // (the plan is only ever used on this stream, so everything after this copy sees it)
+            FLORA_HIP(hipMemcpyAsync(p->d_tables, p->h_tables, tbytes, hipMemcpyHostToDevice, stream));
+        }
+        p->d_items = static_cast<const WorkItem*>(p->d_tables);
+        p->d_items2 = reinterpret_cast<const WorkItem*>(static_cast<char*>(p->d_tables) + off2);
+    }
+    if (wbytes > 0) {
+        if (p->in_arena) p->d_work = arena_take(wbytes);
+        else FLORA_HIP(hipMalloc(&p->d_work, wbytes));
+        p->work_cap = wbytes;
+        // arrival counters start at zero (the kernel leaves them at zero again)
+        if (p->kind == kKindCompress && p->ws_counters > 0)
+            FLORA_HIP(hipMemsetAsync(static_cast<char*>(p->d_work) + round_up(p->ws_floats * 4, 256), 0,
+                                     p->ws_counters * 4, stream));
+    }
+    if (p->in_arena) p->dev_slabs.push_back(arena_take((size_t)kArenaImages * p->mats_bytes));
+    p->placed = true;
     return FLORA_OK;
 }
 
+// Plans the call being prepared needs (caller's workspace only).
+std::vector<Plan*> g_pending;
+
+void drop_plan_at(size_t i)
+{
+    free_plan(g_plans[i]);
+    g_plans.erase(g_plans.begin() + (long)i);
+}
+
 // Finds or creates the plan for (kind, variant, r, shapes, stream) and the device copy of this
-// request's descriptor table; p->cur_mats points at it on return.
-int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipStream_t stream, Plan** out)
+// request's descriptor table; p->cur_mats points at it on return.  With `dry` set (first pass of
+// a call that uses the caller's workspace) the plan is only found or built on the host and noted
+// as needed: nothing is allocated, uploaded or launched.
+int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipStream_t stream, Plan** out,
+             bool dry = false)
 {
     int device = 0;
-    FLORA_HIP(hipGetDevice(&device));
+    if (dry) {
+        // the dry pass is host work only: on a machine without a device the capacity check of
+        // arena_commit is still reached (and reports a workspace that is too small)
+        if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); device = -1; }
+    } else {
+        FLORA_HIP(hipGetDevice(&device));
+    }
     const int count = (int)mats.size();
     const uint64_t sh = hash_shapes(mats);
+    const bool arena = g_ws.base != nullptr;
 
     Plan* p = nullptr;
     for (Plan* q : g_plans)
@@ -552,23 +634,37 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
         }
     if (!p) {
         if ((int)g_plans.size() >= kMaxPlans) {
-            size_t lru = 0;
-            for (size_t i = 1; i < g_plans.size(); ++i)
-                if (g_plans[i]->tick < g_plans[lru]->tick) lru = i;
-            free_plan(g_plans[lru]);
-            g_plans.erase(g_plans.begin() + (long)lru);
+            size_t lru = g_plans.size();
+            for (size_t i = 0; i < g_plans.size(); ++i)
+                if (!g_plans[i]->pending && (lru == g_plans.size() || g_plans[i]->tick < g_plans[lru]->tick)) lru = i;
+            if (lru == g_plans.size()) return FLORA_ERR_INVALID;     // one call needing more than kMaxPlans plans
+            // (a plan dropped from the caller's workspace leaves its bytes unused until the next refill)
+            drop_plan_at(lru);
         }
         p = new Plan();
         p->device = device; p->stream = stream; p->kind = kind; p->variant = variant; p->count = count; p->r = r;
         p->shape_hash = sh;
-        const int st = create_plan(p, mats, stream);
-        if (st != FLORA_OK) {
-            free_plan(p);
-            return st;
+        p->in_arena = arena;
+        build_host_plan(p, mats);
+        if (!arena) {
+            const int st = place_plan(p, stream);
+            if (st != FLORA_OK) {
+                free_plan(p);
+                return st;
+            }
         }
         g_plans.push_back(p);
     }
     p->tick = ++g_tick;
+    if (dry) {
+        if (!p->pending) {
+            p->pending = true;
+            g_pending.push_back(p);
+        }
+        *out = p;
+        return FLORA_OK;
+    }
+    if (!p->placed) return FLORA_ERR_INVALID;      // (cannot happen: arena_commit places what the dry pass noted)
 
     // this request's image: the caller's pointers, the plan's tiling and workspace
     static thread_local std::vector<MatDev> img;
@@ -609,6 +705,7 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
         slot = (int)p->images.size();
         const int slab = slot / p->images_per_slab, within = slot % p->images_per_slab;
         if (slab >= (int)p->dev_slabs.size()) {
+            // (never in the caller's workspace: its one slab of kArenaImages images was placed with the plan)
             void* d = nullptr;
             void* hp = nullptr;
             FLORA_HIP(hipMalloc(&d, p->mats_bytes * (size_t)p->images_per_slab));
@@ -618,8 +715,10 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
         }
         Image im;
         im.d_mats = reinterpret_cast<MatDev*>(static_cast<char*>(p->dev_slabs[(size_t)slab]) + p->mats_bytes * (size_t)within);
-        im.h_stage = static_cast<char*>(p->pin_slabs[(size_t)slab]) + p->mats_bytes * (size_t)within;
-        FLORA_HIP(hipEventCreateWithFlags(&im.ev, hipEventDisableTiming));
+        if (!p->in_arena) {
+            im.h_stage = static_cast<char*>(p->pin_slabs[(size_t)slab]) + p->mats_bytes * (size_t)within;
+            FLORA_HIP(hipEventCreateWithFlags(&im.ev, hipEventDisableTiming));
+        }
         p->images.push_back(std::move(im));
     } else {
         // every slot is taken: the least recently used image gives way.  Kernels that read its
@@ -641,14 +740,101 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
     im.img = img;
     im.hash = h;
     im.tick = g_tick;
-    std::memcpy(im.h_stage, img.data(), ibytes);
-    FLORA_HIP(hipMemcpyAsync(im.d_mats, im.h_stage, ibytes, hipMemcpyHostToDevice, stream));
-    FLORA_HIP(hipEventRecord(im.ev, stream));
-    im.ev_pending = true;
+    if (p->in_arena) {
+        // pageable source: the copy call returns once the source has been staged
+        FLORA_HIP(hipMemcpyAsync(im.d_mats, im.img.data(), ibytes, hipMemcpyHostToDevice, stream));
+    } else {
+        std::memcpy(im.h_stage, img.data(), ibytes);
+        FLORA_HIP(hipMemcpyAsync(im.d_mats, im.h_stage, ibytes, hipMemcpyHostToDevice, stream));
+        FLORA_HIP(hipEventRecord(im.ev, stream));
+        im.ev_pending = true;
+    }
     p->index.emplace(h, slot);
     p->cur_mats = im.d_mats;
     *out = p;
     return FLORA_OK;
+}
+
+// Second half of preparing a call that uses the caller's workspace: the plans the dry pass noted
+// are placed.  If those not yet placed do not fit in what is left, every placed plan is dropped
+// and the workspace refilled from its start with this call's plans; if these alone exceed the
+// workspace the call fails with FLORA_ERR_INVALID and nothing has been enqueued.
+int arena_commit(hipStream_t stream)
+{
+    auto clear_pending = [&]() {
+        for (Plan* p : g_pending) p->pending = false;
+        g_pending.clear();
+    };
+    size_t need_new = 0, need_all = 0;
+    for (Plan* p : g_pending) {
+        need_all += arena_need(*p);
+        if (!p->placed) need_new += arena_need(*p);
+    }
+    if (need_new > g_ws.size - g_ws.used) {
+        if (need_all > g_ws.size) {
+            // also forget the host halves built for this call: they could never be placed
+            for (size_t i = g_plans.size(); i-- > 0;)
+                if (g_plans[i]->pending && !g_plans[i]->placed) drop_plan_at(i);
+            g_pending.clear();
+            for (Plan* p : g_plans) p->pending = false;
+            return FLORA_ERR_INVALID;
+        }
+        for (size_t i = g_plans.size(); i-- > 0;) {
+            Plan* p = g_plans[i];
+            if (!p->in_arena) continue;
+            if (p->pending) {           // stays, but loses its place: tables and images are uploaded again
+                p->placed = false;
+                p->d_tables = nullptr; p->d_work = nullptr; p->d_items = nullptr; p->d_items2 = nullptr;
+                p->dev_slabs.clear(); p->images.clear(); p->index.clear(); p->cur_mats = nullptr;
+            } else {
+                drop_plan_at(i);
+            }
+        }
+        g_ws.used = 0;
+    }
+    for (Plan* p : g_pending)
+        if (!p->placed) {
+            const int st = place_plan(p, stream);
+            if (st != FLORA_OK) {
+                clear_pending();
+                return st;
+            }
+        }
+    clear_pending();
+    return FLORA_OK;
+}
+
+void drop_all_plans()
+{
+    for (Plan* p : g_plans) free_plan(p);
+    g_plans.clear();
+    g_pending.clear();
+}
+
+void abort_pending()
+{
+    for (size_t i = g_plans.size(); i-- > 0;)
+        if (g_plans[i]->pending && !g_plans[i]->placed) drop_plan_at(i);
+    for (Plan* p : g_plans) p->pending = false;
+    g_pending.clear();
+}
+
+// Runs the chunks of one call.  With a caller-owned workspace the chunks are first walked dry (plans
+// found or built on the host and noted), then the workspace's capacity is checked and the plans
+// placed, and only then is anything launched.
+template <typename Body>
+int run_call(hipStream_t s, Body&& body)
+{
+    if (g_ws.base) {
+        int st = body(true);
+        if (st != FLORA_OK) {
+            abort_pending();
+            return st;
+        }
+        st = arena_commit(s);
+        if (st != FLORA_OK) return st;
+    }
+    return body(false);
 }
 
 // ------------------------------------------------------------- validation
@@ -695,7 +881,7 @@ static void fill_seed_args(SeedArgs& sa, const flora_matrix_t* mats, int count, 
 
 // ---- one chunk (count <= kMaxSeedArgs) of each entry point; arguments already validated ----
 static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype, int map,
-                          float a, float b, bool use_next, hipStream_t s)
+                          float a, float b, bool use_next, hipStream_t s, bool dry)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
@@ -707,8 +893,8 @@ static int compress_chunk(const flora_matrix_t* mats, int count, int r, flora_dt
     fill_seed_args(sa, mats, count, use_next);
     const int variant = rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : (grad_dtype == FLORA_BF16 ? 1 : 0);
     Plan* p = nullptr;
-    int st = get_plan(kKindCompress, variant + 4 * map, r, md, s, &p);
-    if (st != FLORA_OK) return st;
+    int st = get_plan(kKindCompress, variant + 4 * map, r, md, s, &p, dry);
+    if (st != FLORA_OK || dry) return st;
     const MatDev* dm = p->cur_mats;
     const WorkItem* di = p->d_items;
     if (variant >= 2) {
@@ -743,7 +929,7 @@ static int run_decompress(Plan* p, const SeedArgs& sa, int r, int mode, int out_
 }
 
 static int decompress_chunk(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
-                            flora_dtype_t out_dtype, hipStream_t s)
+                            flora_dtype_t out_dtype, hipStream_t s, bool dry)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
@@ -754,15 +940,15 @@ static int decompress_chunk(const flora_matrix_t* mats, int count, int r, float 
     SeedArgs sa;
     fill_seed_args(sa, mats, count, false);
     Plan* p = nullptr;
-    int st = get_plan(kKindDecompress, out_dtype == FLORA_BF16 ? 1 : 0, r, md, s, &p);
-    if (st != FLORA_OK) return st;
+    int st = get_plan(kKindDecompress, out_dtype == FLORA_BF16 ? 1 : 0, r, md, s, &p, dry);
+    if (st != FLORA_OK || dry) return st;
     DecompressParams dp{alpha, 0.f, 0.f, 0.f, 0};
     return run_decompress(p, sa, r, kModeOut, out_dtype == FLORA_BF16, dp, s);
 }
 
 // dst == nullptr: state <- state T in place; else dst[l] <- ca * dst[l] + cb * (state T)
 static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* const* dst, float ca, float cb,
-                          hipStream_t s)
+                          hipStream_t s, bool dry)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
@@ -773,8 +959,8 @@ static int transfer_chunk(const flora_matrix_t* mats, int count, int r, float* c
         md[(size_t)l] = M;
     }
     Plan* p = nullptr;
-    int st = get_plan(kKindTransfer, dst ? 1 : 0, r, md, s, &p);
-    if (st != FLORA_OK) return st;
+    int st = get_plan(kKindTransfer, dst ? 1 : 0, r, md, s, &p, dry);
+    if (st != FLORA_OK || dry) return st;
     const MatDev* dm = p->cur_mats;
     const WorkItem* di2 = p->d_items2;
     FLORA_HIP(launch_transfer_T(dm, p->d_items, (int)p->items.size(), count, r, s));
@@ -812,7 +998,7 @@ static int choose_wpolicy(const flora_matrix_t* mats, int count, int r, const fl
 }
 
 static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16, const flora_update_t* u,
-                        int wpolicy, bool use_next, hipStream_t s)
+                        int wpolicy, bool use_next, hipStream_t s, bool dry)
 {
     const bool factored = u->rule == FLORA_RULE_FACTORED, unfactored = u->rule == FLORA_RULE_UNFACTORED;
     const bool scaled = (factored || unfactored) && u->scale_parameter != 0;
@@ -832,8 +1018,8 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16,
     fill_seed_args(sa, mats, count, use_next);
     Plan* p = nullptr;
     const int kind = (factored || unfactored) ? kKindFactored : kKindDecompress;
-    int st = get_plan(kind, (unfactored ? 3 : 2) + (wbf16 ? 4 : 0), r, md, s, &p);
-    if (st != FLORA_OK) return st;
+    int st = get_plan(kind, (unfactored ? 3 : 2) + (wbf16 ? 4 : 0), r, md, s, &p, dry);
+    if (st != FLORA_OK || dry) return st;
     const MatDev* dm = p->cur_mats;
     if (u->rule == FLORA_RULE_SGD) {
         DecompressParams dp{u->alpha, u->lr * u->alpha, 0.f, 0.f, wpolicy};
@@ -864,7 +1050,7 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16,
     return FLORA_OK;
 }
 
-static int sumsq_chunk(const flora_matrix_t* mats, int count, int wbf16, hipStream_t s)
+static int sumsq_chunk(const flora_matrix_t* mats, int count, int wbf16, hipStream_t s, bool dry)
 {
     std::vector<MatDev> md((size_t)count);
     for (int l = 0; l < count; ++l) {
@@ -874,8 +1060,8 @@ static int sumsq_chunk(const flora_matrix_t* mats, int count, int wbf16, hipStre
         md[(size_t)l] = M;
     }
     Plan* p = nullptr;
-    int st = get_plan(kKindSumsq, wbf16, 0, md, s, &p);
-    if (st != FLORA_OK) return st;
+    int st = get_plan(kKindSumsq, wbf16, 0, md, s, &p, dry);
+    if (st != FLORA_OK || dry) return st;
     FLORA_HIP(launch_weight_sumsq(p->cur_mats, count, wbf16, static_cast<float*>(p->d_work), s));
     return FLORA_OK;
 }
@@ -934,11 +1120,14 @@ int flora_compress(const flora_matrix_t* mats, int count, int r, flora_dtype_t g
     st = check_grads(mats, count, grad_dtype);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, false, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, false, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_compress_mapped(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
@@ -950,11 +1139,14 @@ int flora_compress_mapped(const flora_matrix_t* mats, int count, int r, flora_dt
     st = check_grads(mats, count, grad_dtype);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = compress_chunk(mats + c0, cn, r, grad_dtype, (int)map, a, b, false, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = compress_chunk(mats + c0, cn, r, grad_dtype, (int)map, a, b, false, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha, void* const* out,
@@ -967,11 +1159,14 @@ int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha, 
     for (int l = 0; l < count; ++l)
         if (!out[l] || !aligned16(out[l]) || out[l] == (void*)mats[l].state) return FLORA_ERR_INVALID;
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = decompress_chunk(mats + c0, cn, r, alpha, out + c0, out_dtype, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = decompress_chunk(mats + c0, cn, r, alpha, out + c0, out_dtype, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream)
@@ -979,11 +1174,14 @@ int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* 
     int st = check_common(mats, count, r);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_transfer_accumulate(const flora_matrix_t* mats, int count, int r, float a, float b,
@@ -995,11 +1193,14 @@ int flora_transfer_accumulate(const flora_matrix_t* mats, int count, int r, floa
     for (int l = 0; l < count; ++l)
         if (!dst[l] || !aligned16(dst[l]) || dst[l] == mats[l].state) return FLORA_ERR_INVALID;
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = transfer_chunk(mats + c0, cn, r, dst + c0, a, b, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = transfer_chunk(mats + c0, cn, r, dst + c0, a, b, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype_t weight_dtype,
@@ -1008,12 +1209,15 @@ int flora_apply_update(const flora_matrix_t* mats, int count, int r, flora_dtype
     int st = check_update(mats, count, r, weight_dtype, u);
     if (st != FLORA_OK) return st;
     std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int wpolicy = choose_wpolicy(mats, count, r, u, weight_dtype == FLORA_BF16);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, wpolicy, false, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, wpolicy, false, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype,
@@ -1028,17 +1232,20 @@ int flora_fused_step(const flora_matrix_t* mats, int count, int r, flora_dtype_t
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool next = do_transfer != 0;
     const int wpolicy = choose_wpolicy(mats, count, r, u, weight_dtype == FLORA_BF16);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        if (next) {
-            st = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s);
-            if (st != FLORA_OK) return st;
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            int st2 = FLORA_OK;
+            if (next) {
+                st2 = transfer_chunk(mats + c0, cn, r, nullptr, 0.f, 1.f, s, dry);
+                if (st2 != FLORA_OK) return st2;
+            }
+            st2 = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, next, s, dry);
+            if (st2 != FLORA_OK) return st2;
+            st2 = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, wpolicy, next, s, dry);
+            if (st2 != FLORA_OK) return st2;
         }
-        st = compress_chunk(mats + c0, cn, r, grad_dtype, 0, a, b, next, s);
-        if (st != FLORA_OK) return st;
-        st = update_chunk(mats + c0, cn, r, weight_dtype == FLORA_BF16, u, wpolicy, next, s);
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+        return (int)FLORA_OK;
+    });
 }
 
 int flora_weight_sumsq(const flora_matrix_t* mats, int count, flora_dtype_t weight_dtype, void* hip_stream)
@@ -1052,11 +1259,14 @@ int flora_weight_sumsq(const flora_matrix_t* mats, int count, flora_dtype_t weig
             return FLORA_ERR_INVALID;
     }
     std::lock_guard<std::mutex> guard(g_lock);
-    FLORA_FOR_CHUNKS(count, c0, cn) {
-        const int st = sumsq_chunk(mats + c0, cn, weight_dtype == FLORA_BF16, static_cast<hipStream_t>(hip_stream));
-        if (st != FLORA_OK) return st;
-    }
-    return FLORA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return run_call(s, [&](bool dry) {
+        FLORA_FOR_CHUNKS(count, c0, cn) {
+            const int st2 = sumsq_chunk(mats + c0, cn, weight_dtype == FLORA_BF16, s, dry);
+            if (st2 != FLORA_OK) return st2;
+        }
+        return (int)FLORA_OK;
+    });
 }
 
 void flora_adafactor_schedule(uint64_t t, float* rho, float* beta2)
@@ -1137,33 +1347,66 @@ void flora_derive_seeds(uint64_t global_seed, uint64_t first_matrix_id, int coun
     for (int i = 0; i < count; ++i) seeds_out[i] = flora_derive_seed(global_seed, first_matrix_id + (uint64_t)i, epoch);
 }
 
+// Bytes of a caller-owned workspace one plan of this kind would occupy (host work only).
+static size_t plan_need(int kind, int variant, int r, const flora_matrix_t* mats, int count)
+{
+    Plan p;
+    p.kind = kind; p.variant = variant; p.r = r; p.count = count;
+    std::vector<MatDev> md((size_t)count);
+    for (int l = 0; l < count; ++l) { md[(size_t)l].n = mats[l].n; md[(size_t)l].m = mats[l].m; }
+    build_host_plan(&p, md);
+    return arena_need(p);
+}
+
 size_t flora_workspace_bytes(const flora_matrix_t* mats, int count, int r)
 {
     if (!mats || count <= 0 || r <= 0) return 0;
+    if (!rank_f32(r) && !rank_bf16(r)) return 0;
+    for (int l = 0; l < count; ++l)
+        if (mats[l].n < 1 || mats[l].m < 1 || mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24)) return 0;
     std::lock_guard<std::mutex> guard(g_lock);      // reads the tuning knobs
-    std::vector<MatDev> md((size_t)count);
-    size_t items = 0;
-    for (int l = 0; l < count; ++l) {
-        MatDev M{};
-        M.n = mats[l].n; M.m = mats[l].m;
-        if (M.n < 1 || M.m < 1) return 0;
-        md[(size_t)l] = M;
+    // The most demanding call is flora_fused_step with a transfer and an Adafactor rule: its
+    // transfer, compress and update plans are resident together, for every chunk of the call.
+    size_t step = 0, sumsq = 0;
+    FLORA_FOR_CHUNKS(count, c0, cn) {
+        size_t comp = 0;
+        if (rank_bf16(r)) comp = std::max(plan_need(kKindCompress, 2, r, mats + c0, cn), plan_need(kKindCompress, 3, r, mats + c0, cn));
+        else comp = plan_need(kKindCompress, 0, r, mats + c0, cn);
+        step += comp + plan_need(kKindFactored, 2, r, mats + c0, cn) + plan_need(kKindTransfer, 0, r, mats + c0, cn);
+        sumsq += plan_need(kKindSumsq, 0, 0, mats + c0, cn);
     }
-    // the fewest rows per workgroup either decompress kernel would choose for this set
-    const int rows = std::min(choose_decompress_rows(md, kDecompressCols, r), choose_decompress_rows(md, kDecompressColsVec, r));
-    for (MatDev& M : md) {
-        M.nrowblocks = (int)((M.n + rows - 1) / rows);
-        M.ncolchunks = (int)((M.m + kDecompressCols - 1) / kDecompressCols);
-        M.nitems = M.nrowblocks * M.ncolchunks;
-        items += (size_t)M.nitems;
+    return std::max(step, sumsq);
+}
+
+int flora_set_workspace(void* dev_ptr, size_t bytes)
+{
+    if ((dev_ptr == nullptr) != (bytes == 0)) return FLORA_ERR_INVALID;
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u)) return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    // plans placed in the old workspace, or in memory of the library's own, are dropped: from here on
+    // every plan lives where this call says
+    drop_all_plans();
+    g_ws = Arena{};
+    g_ws.base = static_cast<char*>(dev_ptr);
+    g_ws.size = bytes / 256 * 256;
+    return FLORA_OK;
+}
+
+int64_t flora_debug_plan_bytes(int plan_kind, const flora_matrix_t* mats, int count, int r, flora_dtype_t grad_dtype)
+{
+    if (count <= 0 || !mats || plan_kind < 0 || plan_kind > 4 || count > kMaxSeedArgs) return FLORA_ERR_INVALID;
+    if (plan_kind != 4 && !rank_f32(r) && !rank_bf16(r)) return FLORA_ERR_UNSUPPORTED;
+    for (int l = 0; l < count; ++l)
+        if (mats[l].n < 1 || mats[l].m < 1 || mats[l].n > 0x7fffffffLL - 1024 || mats[l].m > (1LL << 24))
+            return FLORA_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_lock);
+    switch (plan_kind) {
+    case 0: return (int64_t)plan_need(kKindCompress, rank_bf16(r) ? (grad_dtype == FLORA_BF16 ? 2 : 3) : 0, r, mats, count);
+    case 1: return (int64_t)plan_need(kKindDecompress, 0, r, mats, count);
+    case 2: return (int64_t)plan_need(kKindTransfer, 0, r, mats, count);
+    case 3: return (int64_t)plan_need(kKindFactored, 2, r, mats, count);
+    default: return (int64_t)plan_need(kKindSumsq, 0, 0, mats, count);
     }
-    size_t transfer = 0;
-    for (const MatDev& M : md) {
-        transfer += round_up((size_t)r * r * 4, 256);
-        if (r >= 64) transfer += round_up((size_t)((M.m + kTransferChunk - 1) / kTransferChunk) * r * r * 4, 256);
-    }
-    return transfer + workspace_bytes_for(md, kKindFactored, r) +
-           sizeof(MatDev) * (size_t)count + sizeof(WorkItem) * items;
 }
 
 int flora_set_tuning(const char* name, int value)
@@ -1196,8 +1439,8 @@ int flora_set_tuning(const char* name, int value)
         return FLORA_ERR_INVALID;
     }
     // cached work tables were built for the old shapes
-    for (Plan* p : g_plans) free_plan(p);
-    g_plans.clear();
+    drop_all_plans();
+    g_ws.used = 0;
     return FLORA_OK;
 }
 
@@ -1217,10 +1460,10 @@ const char* flora_status_string(int status)
 void flora_shutdown(void)
 {
     std::lock_guard<std::mutex> guard(g_lock);
-    for (Plan* p : g_plans) free_plan(p);
-    g_plans.clear();
+    drop_all_plans();
+    g_ws = Arena{};
 }
 
-int flora_version(void) { return 300; }
+int flora_version(void) { return 400; }
 
 }  // extern "C"

@@ -113,6 +113,10 @@ def lib():
         L.flora_derive_seeds.restype = None
         L.flora_workspace_bytes.argtypes = [MP, ci, ci]
         L.flora_workspace_bytes.restype = ctypes.c_size_t
+        L.flora_debug_plan_bytes.argtypes = [ci, MP, ci, ci, ci]
+        L.flora_debug_plan_bytes.restype = ctypes.c_int64
+        L.flora_set_workspace.argtypes = [vp, ctypes.c_size_t]
+        L.flora_set_workspace.restype = ci
         L.flora_set_tuning.argtypes = [ctypes.c_char_p, ci]
         L.flora_set_tuning.restype = ci
         L.flora_last_device_error.argtypes = []
@@ -132,7 +136,8 @@ EXPORTS = [
     "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
     "flora_debug_work_items", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
-    "flora_workspace_bytes", "flora_set_tuning",
+    "flora_workspace_bytes", "flora_set_workspace", "flora_set_tuning",
+    "flora_debug_plan_bytes",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
 
@@ -195,6 +200,14 @@ def decompress(mats, r: int, alpha: float, outs, out_dtype: int, stream=None):
 
 def momentum_transfer(mats, r: int, stream=None):
     _check(lib().flora_momentum_transfer(mats, len(mats), r, _stream(stream)), "flora_momentum_transfer")
+
+
+def debug_plan_bytes(plan_kind: int, shapes, r: int, grad_dtype: int = F32) -> int:
+    mats = matrices(shapes)
+    n = int(lib().flora_debug_plan_bytes(plan_kind, mats, len(mats), r, grad_dtype))
+    if n < 0:
+        raise FloraError(n, "flora_debug_plan_bytes")
+    return n
 
 
 def transfer_accumulate(mats, r: int, a: float, b: float, dsts, stream=None):
@@ -264,6 +277,17 @@ def fields(mats):
 
 def workspace_bytes(mats, r: int) -> int:
     return int(lib().flora_workspace_bytes(mats, len(mats), r))
+
+
+def set_workspace(buf, nbytes: int = 0):
+    """Hands the library a caller-owned device buffer (a torch tensor or a raw address) for all its
+    private device memory; ``set_workspace(None)`` returns to library-allocated memory."""
+    if buf is None:
+        _check(lib().flora_set_workspace(None, 0), "flora_set_workspace")
+        return
+    if not nbytes:
+        nbytes = buf.numel() * buf.element_size()
+    _check(lib().flora_set_workspace(_ptr(buf), nbytes), "flora_set_workspace")
 
 
 def sgd_update(lr: float, alpha: float = 1.0, zero_state_after: bool = False, step_weight_mib: float = 0.0) -> Update:

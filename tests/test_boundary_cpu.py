@@ -171,3 +171,64 @@ def test_adafactor_rules_validation_and_schedule_helper():
     assert flora.adafactor_schedule(32)[1] == pytest.approx(0.9375, rel=1e-6)
     assert flora.adafactor_schedule(40000)[0] == pytest.approx(5e-3, rel=1e-6)
     L.flora_adafactor_schedule(5, None, None)          # NULL outputs are allowed
+
+
+# ---- caller-owned workspace: sizes and validation (host only) --------------------------------
+def _round256(x):
+    return (x + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("index,r", [(2, 16), (3, 64), (5, 256), (1, 8)])
+def test_workspace_bytes_is_the_sum_of_the_fused_steps_plans(index, r):
+    wl = workloads.workload(index)
+    shapes = wl.shapes
+    mats = flora.matrices(shapes)
+    total = flora.workspace_bytes(mats, r)
+    comp = max(flora.debug_plan_bytes(0, shapes, r, flora.BF16), flora.debug_plan_bytes(0, shapes, r, flora.F32))
+    parts = comp + flora.debug_plan_bytes(3, shapes, r) + flora.debug_plan_bytes(2, shapes, r)
+    assert total == max(parts, flora.debug_plan_bytes(4, shapes, r))
+    assert total % 256 == 0 and total > 0
+    # a plan = its work tables (48 bytes per workgroup) + its work area + 8 descriptor images
+    items, info = flora.debug_work_items(1, shapes, r)
+    image = _round256(152 * len(shapes))
+    assert flora.debug_plan_bytes(1, shapes, r) == _round256(48 * len(items)) + 8 * image
+    gdt = flora.F32 if wl.grad_dtype == "f32" else flora.BF16
+    items, info = flora.debug_work_items(0, shapes, r, gdt)
+    work = _round256(4 * int(info[3])) + 4 * int(info[4])
+    assert flora.debug_plan_bytes(0, shapes, r, gdt) == _round256(48 * len(items)) + _round256(work) + 8 * image
+    # the transfer's work area: T per matrix, and at ranks >= 64 one partial per chunk of 1024 columns
+    t_items, _ = flora.debug_work_items(3, shapes, r)
+    a_items, _ = flora.debug_work_items(2, shapes, r)
+    twork = sum(_round256(4 * r * r) + (_round256(4 * r * r * ((m + 1023) // 1024)) if r >= 64 else 0) for _, m in shapes)
+    assert flora.debug_plan_bytes(2, shapes, r) == (_round256(48 * len(t_items)) + _round256(48 * len(a_items))
+                                                    + twork + 8 * image)
+
+
+def test_workspace_bytes_rejects_bad_sets():
+    assert flora.workspace_bytes(flora.matrices([(0, 4)]), 16) == 0
+    assert flora.workspace_bytes(flora.matrices([(4, 4)]), 12) == 0
+    assert flora.lib().flora_workspace_bytes(None, 1, 16) == 0
+
+
+def test_set_workspace_validation_and_too_small_is_refused_before_any_device_work():
+    L = flora.lib()
+    try:
+        assert L.flora_set_workspace(0x10001, 4096) == flora.ERR_INVALID         # not 256-byte aligned
+        assert L.flora_set_workspace(None, 4096) == flora.ERR_INVALID
+        assert L.flora_set_workspace(0x10000, 0) == flora.ERR_INVALID
+        # a (fake) workspace of one unit: every call needs more, and says so on the host, before
+        # the device is touched (the addresses here are never dereferenced)
+        assert L.flora_set_workspace(0x10000, 256) == flora.OK
+        ok = _mats(n=64, m=64, rs=0x4000, cs=0x5000)
+        upd = flora.sgd_update(1e-3)
+        assert L.flora_compress(ok, 1, 16, flora.F32, 1.0, 1.0, None) == flora.ERR_INVALID
+        assert L.flora_apply_update(ok, 1, 16, flora.F32, ctypes.byref(upd), None) == flora.ERR_INVALID
+        assert L.flora_momentum_transfer(ok, 1, 16, None) == flora.ERR_INVALID
+        assert L.flora_fused_step(ok, 1, 16, flora.F32, flora.F32, 0.9, 0.1, 1, ctypes.byref(upd), None) == flora.ERR_INVALID
+        # one unit short of what the fused step needs is refused as well
+        need = flora.workspace_bytes(ok, 16)
+        fac = flora.factored_update(1e-3, 1.0, 0.0, 1e-30, 1.0)
+        assert L.flora_set_workspace(0x10000, need - 256) == flora.OK
+        assert L.flora_fused_step(ok, 1, 16, flora.F32, flora.F32, 0.9, 0.1, 1, ctypes.byref(fac), None) == flora.ERR_INVALID
+    finally:
+        assert L.flora_set_workspace(None, 0) == flora.OK
