@@ -86,7 +86,8 @@ typedef enum {
     FLORA_OK = 0,
     FLORA_ERR_INVALID = -1,      /* null pointer, n/m/count out of range, bad enum, misaligned pointer */
     FLORA_ERR_UNSUPPORTED = -2,  /* valid request with no kernel (rank or dtype outside the list above) */
-    FLORA_ERR_DEVICE = -3        /* a HIP call failed; see flora_last_device_error()                    */
+    FLORA_ERR_DEVICE = -3,       /* a HIP call failed; see flora_last_device_error()                    */
+    FLORA_ERR_TOO_LARGE = -4     /* flora_momentum_transfer_static: the request needs more than the fixed buffer */
 } flora_status_t;
 
 /* One weight matrix.  Fields a given call does not use may be NULL / 0. */
@@ -163,6 +164,24 @@ int flora_decompress(const flora_matrix_t* mats, int count, int r, float alpha,
  * entirely in fp32.  Uses state, n, m, seed, seed_next.  The caller replaces
  * seed by seed_next afterwards. */
 int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* hip_stream);
+
+/* For callers that cannot allocate: code under HIP graph capture preparation, tight serving or
+ * training loops, harnesses that forbid hipMalloc.  The same operation, arguments, requirements
+ * and results (bit for bit) as flora_momentum_transfer, but the device memory it needs beyond M
+ * itself -- descriptor table, work tables, the r x r matrices T and their per-chunk partials --
+ * lives in a fixed array of FLORA_STATIC_SCRATCH_BYTES bytes inside the library, one copy per
+ * GPU, held until the process ends.  The call allocates nothing on the device or in pinned memory
+ * (no hipMalloc, hipHostMalloc, hipFree) and ignores flora_set_workspace; it uploads its tables
+ * with one asynchronous copy from pageable host memory and launches the transfer's kernels.
+ * A request needs  sum over matrices of (1 + [r >= 64] ceil(m / 1024)) * 4 r^2  bytes, rounded up
+ * to 256 per term, plus 152 bytes per matrix and 48 bytes per workgroup (about 2 MiB per matrix
+ * at r = 256, m = 6400; 16 KiB at r <= 32): beyond the array's size, or with count > 448, the
+ * call returns FLORA_ERR_TOO_LARGE and nothing has been enqueued.  All calls on one GPU share that
+ * GPU's array and each overwrites what the last one left: calls that may run at the same time on
+ * one GPU (different streams, different host threads' streams) race and must be ordered by the
+ * caller. */
+#define FLORA_STATIC_SCRATCH_BYTES (32u << 20)
+int flora_momentum_transfer_static(const flora_matrix_t* mats, int count, int r, void* hip_stream);
 
 /* A compressed accumulator folded into a compressed moving average kept under another
  * projection (Algorithm 1's decompressed mean fed to Algorithm 2's EMA line: a = beta,

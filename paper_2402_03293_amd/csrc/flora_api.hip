@@ -1453,6 +1453,7 @@ const char* flora_status_string(int status)
     case FLORA_ERR_INVALID: return "invalid argument";
     case FLORA_ERR_UNSUPPORTED: return "unsupported rank or dtype";
     case FLORA_ERR_DEVICE: return "HIP call failed";
+    case FLORA_ERR_TOO_LARGE: return "request exceeds the entry point's fixed scratch buffer";
     default: return "unknown status";
     }
 }
@@ -1467,3 +1468,79 @@ void flora_shutdown(void)
 int flora_version(void) { return 400; }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// flora_momentum_transfer_static: the momentum transfer for callers that cannot allocate.  The
+// device memory the transfer needs beyond M itself (descriptor table, work tables, the r x r
+// matrices T and their per-chunk partials) lives in this fixed array instead of in allocated
+// memory.  Every GPU the library runs on holds its own copy of the array, at its own address,
+// until the process ends.
+static __device__ __align__(256) unsigned char scratch[FLORA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+unsigned char* g_scratch_ptr[kMaxScratchDevices] = {};   // device address of `scratch`, per device
+Plan g_static_plan;                                      // host tables of the current call (capacity is reused)
+std::vector<char> g_static_stage;                        // image + tables, source of the one upload
+}  // namespace
+
+extern "C" int flora_momentum_transfer_static(const flora_matrix_t* mats, int count, int r, void* hip_stream)
+{
+    int st = check_common(mats, count, r);
+    if (st != FLORA_OK) return st;
+    if (count == 0) return FLORA_OK;
+    if (count > kMaxSeedArgs) return FLORA_ERR_TOO_LARGE;
+    std::lock_guard<std::mutex> guard(g_lock);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    // host tables and sizes (no device work yet)
+    Plan& p = g_static_plan;
+    p.kind = kKindTransfer; p.variant = 0; p.r = r; p.count = count;
+    p.items.clear(); p.items2.clear();
+    static std::vector<MatDev> md;
+    md.assign((size_t)count, MatDev{});
+    for (int l = 0; l < count; ++l) {
+        MatDev& M = md[(size_t)l];
+        M.state = mats[l].state; M.n = mats[l].n; M.m = mats[l].m;
+        fill_seed(M, mats[l]);
+    }
+    build_host_plan(&p, md);
+    const size_t need = p.mats_bytes + round_up(p.tbytes, 256) + round_up(p.wbytes, 256);
+    if (need > (size_t)FLORA_STATIC_SCRATCH_BYTES) return FLORA_ERR_TOO_LARGE;
+
+    // this device's copy of the array
+    int device = 0;
+    FLORA_HIP(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxScratchDevices) return FLORA_ERR_UNSUPPORTED;
+    if (!g_scratch_ptr[device]) {
+        void* sp = nullptr;
+        FLORA_HIP(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[device] = static_cast<unsigned char*>(sp);
+    }
+    unsigned char* base = g_scratch_ptr[device];
+    unsigned char* d_tab = base + p.mats_bytes;
+    unsigned char* w = d_tab + round_up(p.tbytes, 256);
+    for (int l = 0; l < count; ++l) {
+        MatDev& M = md[(size_t)l];
+        M.ncolchunks = p.host_mats[(size_t)l].ncolchunks;
+        M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256);
+        if (r >= 64) { M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * r * r * 4, 256); }
+    }
+    // descriptor image and both work tables in one copy from pageable memory (the call returns
+    // once the source has been staged, so the buffer can be reused by the next call)
+    const size_t up = p.mats_bytes + p.tbytes;
+    g_static_stage.assign(up, 0);
+    std::memcpy(g_static_stage.data(), md.data(), sizeof(MatDev) * (size_t)count);
+    if (!p.items.empty()) std::memcpy(g_static_stage.data() + p.mats_bytes, p.items.data(), sizeof(WorkItem) * p.items.size());
+    if (!p.items2.empty())
+        std::memcpy(g_static_stage.data() + p.mats_bytes + p.off2, p.items2.data(), sizeof(WorkItem) * p.items2.size());
+    FLORA_HIP(hipMemcpyAsync(base, g_static_stage.data(), up, hipMemcpyHostToDevice, s));
+    const MatDev* dm = reinterpret_cast<const MatDev*>(base);
+    const WorkItem* di = reinterpret_cast<const WorkItem*>(d_tab);
+    const WorkItem* di2 = reinterpret_cast<const WorkItem*>(d_tab + p.off2);
+    // T and its partials are written in full before they are read: nothing of the previous call's
+    // contents is used and nothing needs clearing
+    FLORA_HIP(launch_transfer_T(dm, di, (int)p.items.size(), count, r, s));
+    FLORA_HIP(launch_apply_T(dm, di2, (int)p.items2.size(), r, 0.f, 1.f, s));
+    return FLORA_OK;
+}

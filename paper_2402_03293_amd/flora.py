@@ -17,6 +17,8 @@ OK = 0
 ERR_INVALID = -1
 ERR_UNSUPPORTED = -2
 ERR_DEVICE = -3
+ERR_TOO_LARGE = -4
+STATIC_SCRATCH_BYTES = 32 << 20
 RULE_SGD = 0
 RULE_FACTORED = 1
 RULE_UNFACTORED = 2
@@ -113,6 +115,8 @@ def lib():
         L.flora_derive_seeds.restype = None
         L.flora_workspace_bytes.argtypes = [MP, ci, ci]
         L.flora_workspace_bytes.restype = ctypes.c_size_t
+        L.flora_momentum_transfer_static.argtypes = [MP, ci, ci, vp]
+        L.flora_momentum_transfer_static.restype = ci
         L.flora_debug_plan_bytes.argtypes = [ci, MP, ci, ci, ci]
         L.flora_debug_plan_bytes.restype = ctypes.c_int64
         L.flora_set_workspace.argtypes = [vp, ctypes.c_size_t]
@@ -136,7 +140,7 @@ EXPORTS = [
     "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
     "flora_debug_work_items", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
-    "flora_workspace_bytes", "flora_set_workspace", "flora_set_tuning",
+    "flora_workspace_bytes", "flora_set_workspace", "flora_set_tuning", "flora_momentum_transfer_static",
     "flora_debug_plan_bytes",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
 ]
@@ -200,6 +204,11 @@ def decompress(mats, r: int, alpha: float, outs, out_dtype: int, stream=None):
 
 def momentum_transfer(mats, r: int, stream=None):
     _check(lib().flora_momentum_transfer(mats, len(mats), r, _stream(stream)), "flora_momentum_transfer")
+
+
+def momentum_transfer_static(mats, r: int, stream=None):
+    """flora_momentum_transfer_static: the transfer out of the library's fixed scratch array."""
+    _check(lib().flora_momentum_transfer_static(mats, len(mats), r, _stream(stream)), "flora_momentum_transfer_static")
 
 
 def debug_plan_bytes(plan_kind: int, shapes, r: int, grad_dtype: int = F32) -> int:

@@ -232,3 +232,16 @@ def test_set_workspace_validation_and_too_small_is_refused_before_any_device_wor
         assert L.flora_fused_step(ok, 1, 16, flora.F32, flora.F32, 0.9, 0.1, 1, ctypes.byref(fac), None) == flora.ERR_INVALID
     finally:
         assert L.flora_set_workspace(None, 0) == flora.OK
+
+
+def test_static_transfer_rejects_what_its_buffer_cannot_hold():
+    L = flora.lib()
+    assert b"fixed scratch" in L.flora_status_string(flora.ERR_TOO_LARGE)
+    # 20 matrices of 1600 x 6400 at r = 256 need 20 * 8 * 256 KiB = 40 MiB of T and partials
+    big = flora.matrices([(1600, 6400)] * 20, states=[0x3000] * 20, seeds=[1] * 20, seeds_next=[2] * 20)
+    assert L.flora_momentum_transfer_static(big, 20, 256, None) == flora.ERR_TOO_LARGE
+    many = flora.matrices([(8, 8)] * 449, states=[0x3000] * 449)
+    assert L.flora_momentum_transfer_static(many, 449, 8, None) == flora.ERR_TOO_LARGE
+    assert L.flora_momentum_transfer_static(None, 1, 8, None) == flora.ERR_INVALID
+    assert L.flora_momentum_transfer_static(many, 1, 12, None) == flora.ERR_UNSUPPORTED
+    assert L.flora_momentum_transfer_static(many, 0, 8, None) == flora.OK
