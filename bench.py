@@ -76,6 +76,10 @@ def parse_args():
     ap.add_argument("--separate-calls", action="store_true",
                     help="Algorithm-2 workloads: issue every step as flora_compress + flora_apply_update instead "
                          "of flora_fused_step (the same kernels in the same order)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of a workload, time plain kernels that bound the hot path on this chip (streaming "
+                         "read, the compress kernels' operand pattern, copy, register-resident matrix-core loops, the "
+                         "generator alone) and print them as one JSON line")
     ap.add_argument("--cpu-budget-gflop", type=float, default=16.0,
                     help="size of the oracle's sample (fp64 GFLOP)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
@@ -108,6 +112,75 @@ def generated_normals(flora, shapes, r, gdt, kind):
         m = shapes[int(it[0])][1]
         tot += min(colsper, m - int(it[3])) * r
     return tot
+
+
+def ceilings():
+    """What plain kernels reach on this chip (the library's measurement hooks, HIP events on the
+    launch stream, median over the launches)."""
+    import torch
+    from paper_2402_03293_amd import flora
+
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    out = {"what": "ceilings of plain kernels on this chip", "unit_note": "GB = 1e9 bytes", "kernels": {}}
+
+    def time_launches(fn, n):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        ms = []
+        for i in range(n):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn(i)
+            e1.record(stream)
+            ms.append((e0, e1))
+        torch.cuda.synchronize()
+        v = sorted(a.elapsed_time(b) for a, b in ms)
+        return v[len(v) // 2], v[0]
+
+    tiny = torch.zeros(64, dtype=torch.float32, device=dev)
+    med, mn = time_launches(lambda i: flora.debug_read(tiny, 16, sink, 0, 0, 0, stream), 200)
+    out["kernels"]["empty launch"] = {"median_us": med * 1e3, "min_us": mn * 1e3}
+
+    # workload 2's size: 176 MB per launch, a ring of 8 buffers so that nothing is served from cache
+    rows, row_bytes = 21504, 8192
+    small = [torch.zeros(rows * row_bytes // 4, dtype=torch.float32, device=dev) for _ in range(8)]
+    nb = rows * row_bytes
+    for name, pat, chunk in (("stream read, 176 MB", 0, 0), ("operand-pattern read (16 rows x 64 B per instruction, "
+                                                              "2048 B per wave and row), 176 MB", 1, 2048)):
+        med, mn = time_launches(lambda i: flora.debug_read(small[i % 8], nb, sink, pat, row_bytes, chunk, stream), 80)
+        out["kernels"][name] = {"median_us": med * 1e3, "min_us": mn * 1e3, "GBps": nb / (med * 1e-3) / 1e9}
+    del small
+    big = [torch.zeros(1 << 28, dtype=torch.float32, device=dev) for _ in range(3)]
+    nb = 1 << 30
+    for name, pat, chunk, rb in (("stream read, 1 GiB", 0, 0, 0),
+                                 ("operand-pattern read, 1 GiB (rows of 8192 B, 2048 B per wave and row)", 1, 2048, 8192),
+                                 ("operand-pattern read, 1 GiB (rows of 32768 B, whole rows per wave)", 1, 32768, 32768)):
+        med, mn = time_launches(lambda i: flora.debug_read(big[i % 3], nb, sink, pat, rb, chunk, stream), 20)
+        out["kernels"][name] = {"median_us": med * 1e3, "min_us": mn * 1e3, "GBps": nb / (med * 1e-3) / 1e9}
+    med, mn = time_launches(lambda i: flora.debug_copy(big[i % 2], big[2], nb, stream), 20)
+    out["kernels"]["copy, 1 GiB read + 1 GiB written"] = {"median_us": med * 1e3, "min_us": mn * 1e3,
+                                                          "GBps": 2 * nb / (med * 1e-3) / 1e9}
+    del big
+    for name, kind, iters in (("v_mfma_f32_16x16x32_bf16 loop", 0, 20000), ("v_mfma_f32_32x32x16_bf16 loop", 1, 20000),
+                              ("v_mfma_f32_16x16x4_f32 loop", 2, 20000)):
+        work = [0.0]
+
+        def fn(i, kind=kind, iters=iters):
+            work[0] = flora.debug_compute_loop(kind, iters, sink, stream)
+        med, mn = time_launches(fn, 5)
+        out["kernels"][name] = {"median_ms": med, "TFLOPs": work[0] / (med * 1e-3) / 1e12}
+    work = [0.0]
+
+    def gen(i):
+        work[0] = flora.debug_compute_loop(3, 2000, sink, stream)
+    med, mn = time_launches(gen, 5)
+    out["kernels"]["generator alone (Philox4x32-10 + Box-Muller)"] = {"median_ms": med, "normals_per_s": work[0] / (med * 1e-3)}
+    out["published_peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "bf16_mfma_TFLOPs": BF16_MFMA_PEAK_TFLOPS, "fp32_mfma_TFLOPs": 157.3}
+    return out
 
 
 def run_config(args, index, steps, warmup, cpu_seconds, variants=True):
@@ -504,6 +577,10 @@ def main():
             name, val = kv.split("=")
             flora.set_tuning(name, int(val))
     torch.cuda.set_device(0)
+
+    if args.ceilings:
+        print(json.dumps(ceilings()))
+        return
 
     if args.config is not None:
         idx = args.config

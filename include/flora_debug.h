@@ -39,6 +39,22 @@ int64_t flora_debug_plan_bytes(int plan_kind, const flora_matrix_t* mats, int co
  * hot-path kernels are scaled by what they read for this copy of known size. */
 int flora_debug_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
 
+/* Measurement hooks: plain kernels that show what this chip gives a kernel that does nothing but
+ * the one thing, to judge the hot-path kernels against (bench.py --ceilings times them).
+ * flora_debug_read reads `bytes` bytes (a multiple of 16) at src (DEVICE, 16-byte aligned) and
+ * stores nothing (sink: DEVICE, 4 bytes, never written).  pattern 0: contiguous, 16 bytes per lane;
+ * pattern 1: the compress kernels' operand pattern over a matrix of bytes / row_bytes rows: a wave
+ * instruction covers 16 rows x 64 contiguous bytes, a wave owns 16 rows x chunk_bytes (a multiple
+ * of 256 that divides row_bytes), a workgroup 64 rows.
+ * flora_debug_compute_loop launches 2048 workgroups of four waves running `iters` rounds of a
+ * register-resident loop: kind 0 v_mfma_f32_16x16x32_bf16 (8 per round), 1 v_mfma_f32_32x32x16_bf16
+ * (4 per round), 2 v_mfma_f32_16x16x4_f32 (8 per round), 3 the projection's generator (one
+ * Philox4x32-10 + Box-Muller quad per round and thread); *work_out (HOST) receives the flops
+ * (kinds 0-2) or normals (kind 3) the launch performs. */
+int flora_debug_read(const void* src, size_t bytes, int pattern, size_t row_bytes, int chunk_bytes, void* sink,
+                     void* hip_stream);
+int flora_debug_compute_loop(int kind, int iters, void* sink, double* work_out, void* hip_stream);
+
 /* Tuning hook for sweeps: overrides a launch-shape choice the library otherwise makes itself
  * (value 0 restores the default).  Names: "compress_f32_kgroups" (1, 2, 4: column groups per
  * workgroup in the fp32 compress kernel), "compress_f32_mt" (1, 2: rows per workgroup / 64 in

@@ -1332,6 +1332,25 @@ int flora_debug_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
     return FLORA_OK;
 }
 
+int flora_debug_read(const void* src, size_t bytes, int pattern, size_t row_bytes, int chunk_bytes, void* sink,
+                     void* hip_stream)
+{
+    if (!src || !sink || !aligned16(src) || (bytes % 16) != 0 || (pattern != 0 && pattern != 1)) return FLORA_ERR_INVALID;
+    if (pattern == 1 && (row_bytes == 0 || chunk_bytes <= 0 || (chunk_bytes % 256) != 0 || (row_bytes % (size_t)chunk_bytes) != 0 ||
+                         (bytes % row_bytes) != 0))
+        return FLORA_ERR_INVALID;
+    FLORA_HIP(launch_debug_read(src, (long long)bytes, pattern, (long long)row_bytes, chunk_bytes,
+                                static_cast<uint32_t*>(sink), static_cast<hipStream_t>(hip_stream)));
+    return FLORA_OK;
+}
+
+int flora_debug_compute_loop(int kind, int iters, void* sink, double* work_out, void* hip_stream)
+{
+    if (kind < 0 || kind > 3 || iters < 1 || !sink || !work_out) return FLORA_ERR_INVALID;
+    FLORA_HIP(launch_debug_compute_loop(kind, iters, static_cast<float*>(sink), work_out, static_cast<hipStream_t>(hip_stream)));
+    return FLORA_OK;
+}
+
 uint64_t flora_derive_seed(uint64_t global_seed, uint64_t matrix_id, uint64_t epoch)
 {
     const Words4 x = philox4x32_10((uint32_t)matrix_id, (uint32_t)(epoch & 0xffffffffu), (uint32_t)(epoch >> 32),

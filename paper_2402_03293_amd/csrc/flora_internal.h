@@ -224,6 +224,9 @@ __device__ __forceinline__ float store_elem(uint16_t* p, float v)
 hipError_t launch_debug_generate(uint64_t seed, long long m, int r, float* A_out, uint32_t* raw_out,
                                  hipStream_t s);
 hipError_t launch_debug_copy(const void* src, void* dst, long long bytes, hipStream_t s);
+hipError_t launch_debug_read(const void* src, long long bytes, int pattern, long long row_bytes, int chunk_bytes,
+                             uint32_t* sink, hipStream_t s);
+hipError_t launch_debug_compute_loop(int kind, int iters, float* sink, double* work_out, hipStream_t s);
 hipError_t launch_compress_f32(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds,
                                int r, int grad_is_bf16, int map, float a, float b, int kgroups, int mt,
                                float* partials, uint32_t* counters, hipStream_t s);

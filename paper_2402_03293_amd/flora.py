@@ -109,6 +109,10 @@ def lib():
         L.flora_debug_work_items.restype = ctypes.c_int64
         L.flora_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.flora_debug_copy.restype = ci
+        L.flora_debug_read.argtypes = [vp, ctypes.c_size_t, ci, ctypes.c_size_t, ci, vp, vp]
+        L.flora_debug_read.restype = ci
+        L.flora_debug_compute_loop.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.flora_debug_compute_loop.restype = ci
         L.flora_derive_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
         L.flora_derive_seed.restype = ctypes.c_uint64
         L.flora_derive_seeds.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ci, ctypes.c_uint64, vp]
@@ -139,7 +143,7 @@ EXPORTS = [
     "flora_compress", "flora_compress_mapped", "flora_decompress", "flora_momentum_transfer", "flora_transfer_accumulate",
     "flora_apply_update",
     "flora_fused_step", "flora_weight_sumsq", "flora_adafactor_schedule", "flora_debug_generate",
-    "flora_debug_work_items", "flora_debug_copy", "flora_derive_seed", "flora_derive_seeds",
+    "flora_debug_work_items", "flora_debug_copy", "flora_debug_read", "flora_debug_compute_loop", "flora_derive_seed", "flora_derive_seeds",
     "flora_workspace_bytes", "flora_set_workspace", "flora_set_tuning", "flora_momentum_transfer_static",
     "flora_debug_plan_bytes",
     "flora_last_device_error", "flora_status_string", "flora_shutdown", "flora_version",
@@ -259,6 +263,19 @@ def debug_work_items(kind: int, shapes, r: int, grad_dtype: int = F32):
 
 def debug_copy(src, dst, nbytes: int, stream=None):
     _check(lib().flora_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "flora_debug_copy")
+
+
+def debug_read(src, nbytes: int, sink, pattern: int = 0, row_bytes: int = 0, chunk_bytes: int = 0, stream=None):
+    _check(lib().flora_debug_read(_ptr(src), nbytes, pattern, row_bytes, chunk_bytes, _ptr(sink), _stream(stream)),
+           "flora_debug_read")
+
+
+def debug_compute_loop(kind: int, iters: int, sink, stream=None) -> float:
+    """Launches the loop and returns the flops (kinds 0-2) or normals (kind 3) it performs."""
+    work = ctypes.c_double(0.0)
+    _check(lib().flora_debug_compute_loop(kind, iters, _ptr(sink), ctypes.byref(work), _stream(stream)),
+           "flora_debug_compute_loop")
+    return work.value
 
 
 def derive_seed(global_seed: int, matrix_id: int, epoch: int) -> int:
