@@ -174,7 +174,7 @@ int flora_momentum_transfer(const flora_matrix_t* mats, int count, int r, void* 
  * (no hipMalloc, hipHostMalloc, hipFree) and ignores flora_set_workspace; it uploads its tables
  * with one asynchronous copy from pageable host memory and launches the transfer's kernels.
  * A request needs  sum over matrices of (1 + [r >= 64] ceil(m / 1024)) * 4 r^2  bytes, rounded up
- * to 256 per term, plus 152 bytes per matrix and 48 bytes per workgroup (about 2 MiB per matrix
+ * to 256 per term, plus 184 bytes per matrix and 48 bytes per workgroup (about 2 MiB per matrix
  * at r = 256, m = 6400; 16 KiB at r <= 32): beyond the array's size, or with count > 448, the
  * call returns FLORA_ERR_TOO_LARGE and nothing has been enqueued.  All calls on one GPU share that
  * GPU's array and each overwrites what the last one left: calls that may run at the same time on

@@ -64,7 +64,10 @@ int flora_debug_compute_loop(int kind, int iters, void* sink, double* work_out, 
  * share the columns of a row block between workgroups of about this many columns each), "decompress_rows" (a multiple of 32: rows per workgroup in the
  * decompress / update kernels), "decompress_vec" (1: always the 4-byte-per-lane kernel at
  * ranks >= 64, 2: the 16-byte-per-lane kernel whenever every m is a multiple of 4, which is
- * also the default), "update_wpolicy" (the update passes: 1 plain
+ * also the default), "factored_gram" (the factored rule at ranks >= 64: 1 reduction passes over the decompressed
+ * gradient, 2 quadratic forms in r x r Gram matrices; by default whichever is less arithmetic for the
+ * set), "gram_chunk" (a multiple of 64: entries of m or n per workgroup of the Gram sums),
+ * "update_wpolicy" (the update passes: 1 plain
  * accesses to the weights, 2 reads with the non-temporal hint, 3 writes with it, 4 both; by
  * default chosen from the size of the call's weights against the 256 MB last-level cache: a
  * caller that updates a large model a few matrices per call may want 4).  Results never depend

@@ -23,6 +23,7 @@ SOURCES = [
     "flora_decompress_f32.hip",
     "flora_decompress_bf16.hip",
     "flora_transfer.hip",
+    "flora_gram.hip",
     "flora_small.hip",
 ]
 

@@ -106,6 +106,10 @@ struct Plan {
     size_t tbytes = 0;                  // bytes of the tables
     size_t wbytes = 0;                  // bytes of the work area
     bool pending = false;               // needed by the call being prepared (caller's workspace)
+    // factored rule through Gram matrices: items2 = [Gram sums over m | over n | quadratic forms over the
+    // rows of S | over the rows of A]
+    bool gram = false;
+    int n_gm = 0, n_gn = 0, n_qr = 0, n_qc = 0;
 };
 
 // Caller-owned workspace (flora_set_workspace).  While one is set every device buffer of a plan
@@ -132,6 +136,9 @@ struct Tuning {
     int decompress_rows = 0;        // decompress / update: rows per workgroup, a multiple of 32
     int decompress_vec = -1;        // bf16 decompress: -1 choose, 0 scalar kernel, 1 vector kernel when aligned
     int update_wpolicy = 0;         // update passes: 0 choose; 1 + (bit 0 stream reads of W, bit 1 stream writes)
+    int factored_gram = 0;          // factored rule at ranks >= 64: 0 choose; 1 reduction passes over the n x m
+                                    // product; 2 quadratic forms in r x r Gram matrices
+    int gram_chunk = 0;             // long-index entries per workgroup of the Gram sums (0: kGramChunk)
 };
 Tuning g_tune;
 
@@ -466,10 +473,76 @@ void build_transfer_T_items(Plan& p)
     }
 }
 
-size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r)
+// The factored rule's reduction passes as quadratic forms in Gram matrices (flora_gram.hip): chosen
+// when that is clearly less arithmetic than two passes over the n x m product, 6 (m + n) r^2 against
+// 4 n m r flops per matrix (with a margin: kernels with r x r outputs and split sums run the
+// matrix cores less efficiently than the long sweeps of the decompression).
+bool choose_gram(const Plan& p)
+{
+    if (!rank_bf16(p.r)) return false;
+    if (g_tune.factored_gram) return g_tune.factored_gram == 2;
+    double pass = 0.0, gram = 0.0;
+    for (const MatDev& M : p.host_mats) {
+        pass += 4.0 * (double)M.n * (double)M.m * p.r;
+        gram += 6.0 * ((double)M.n + (double)M.m) * p.r * p.r;
+    }
+    return 1.5 * gram < pass;
+}
+
+void build_gram_items(Plan& p)
+{
+    const long long gchunk = g_tune.gram_chunk ? g_tune.gram_chunk : kGramChunk;
+    auto chunks_of = [&](long long len) { return (int)((len + gchunk - 1) / gchunk); };
+    auto emit_chunks = [&](int l, long long len, int chunks) {
+        const long long per = ((len + chunks - 1) / chunks + 63) / 64 * 64;
+        for (int c = 0; c < chunks; ++c) {
+            WorkItem w{};
+            w.mat = l; w.part = c;
+            w.col0 = (int)std::min<long long>(len, (long long)c * per);
+            w.col1 = (int)std::min<long long>(len, (long long)(c + 1) * per);
+            p.items2.push_back(w);
+        }
+    };
+    auto emit_blocks = [&](int l, long long len) {
+        const long long nb = (len + kQuadformRows - 1) / kQuadformRows;
+        const long long per = ((len + nb - 1) / nb + 31) / 32 * 32;
+        int b = 0;
+        for (long long r0 = 0; r0 < len; r0 += per, ++b) {
+            WorkItem w{};
+            w.mat = l; w.part = b; w.row0 = (int)r0; w.rows = (int)std::min<long long>(per, len - r0);
+            p.items2.push_back(w);
+        }
+        return b;
+    };
+    for (int l = 0; l < p.count; ++l) {
+        MatDev& M = p.host_mats[(size_t)l];
+        M.gchunks_m = chunks_of(M.m);
+        M.gchunks_n = chunks_of(M.n);
+    }
+    // longest first within each table
+    std::vector<int> by_m(p.count), by_n(p.count);
+    for (int i = 0; i < p.count; ++i) by_m[i] = by_n[i] = i;
+    std::stable_sort(by_m.begin(), by_m.end(), [&](int a, int b) { return p.host_mats[a].m > p.host_mats[b].m; });
+    std::stable_sort(by_n.begin(), by_n.end(), [&](int a, int b) { return p.host_mats[a].n > p.host_mats[b].n; });
+    size_t before = p.items2.size();
+    for (int l : by_m) emit_chunks(l, p.host_mats[(size_t)l].m, p.host_mats[(size_t)l].gchunks_m);
+    p.n_gm = (int)(p.items2.size() - before); before = p.items2.size();
+    for (int l : by_n) emit_chunks(l, p.host_mats[(size_t)l].n, p.host_mats[(size_t)l].gchunks_n);
+    p.n_gn = (int)(p.items2.size() - before); before = p.items2.size();
+    for (int l : by_n) p.host_mats[(size_t)l].item0 = emit_blocks(l, p.host_mats[(size_t)l].n);
+    p.n_qr = (int)(p.items2.size() - before); before = p.items2.size();
+    for (int l : by_m) (void)emit_blocks(l, p.host_mats[(size_t)l].m);
+    p.n_qc = (int)(p.items2.size() - before);
+}
+
+size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r, bool gram = false)
 {
     size_t b = 0;
     for (const MatDev& M : mats) {
+        if (kind == kKindFactored && gram) {
+            b += 2 * round_up((size_t)r * r * 2, 256);
+            b += round_up((size_t)std::max(M.gchunks_m, M.gchunks_n) * r * r * 4, 256);
+        }
         if (kind == kKindTransfer) {
             b += round_up((size_t)r * r * 4, 256);
             if (r >= 64) b += round_up((size_t)M.ncolchunks * r * r * 4, 256);
@@ -535,10 +608,14 @@ void build_host_plan(Plan* p, const std::vector<MatDev>& mats)
         build_apply_T_items(*p);
     } else if (kind != kKindSumsq) {
         build_decompress_items(*p);
+        if (kind == kKindFactored && (p->variant & 3) == 2) {     // the factored rule (not the unfactored one)
+            p->gram = choose_gram(*p);
+            if (p->gram) build_gram_items(*p);
+        }
     }
     p->off2 = round_up(sizeof(WorkItem) * p->items.size(), 256);
     p->tbytes = p->off2 + round_up(sizeof(WorkItem) * p->items2.size(), 256);
-    p->wbytes = workspace_bytes_for(p->host_mats, kind, r);
+    p->wbytes = workspace_bytes_for(p->host_mats, kind, r, p->gram);
     if (kind == kKindCompress) p->wbytes = round_up(p->ws_floats * 4, 256) + p->ws_counters * 4;
     p->mats_bytes = round_up(sizeof(MatDev) * (size_t)count, 256);
     // descriptor images kept per plan: many for calls on a few matrices (a training loop that
@@ -675,6 +752,13 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
             MatDev& M = img[(size_t)l];
             const MatDev& t = p->host_mats[(size_t)l];
             M.ncolchunks = t.ncolchunks; M.nrowblocks = t.nrowblocks; M.item0 = t.item0; M.nitems = t.nitems;
+            M.gchunks_m = t.gchunks_m; M.gchunks_n = t.gchunks_n;
+            if (kind == kKindFactored && p->gram) {
+                M.gramP = reinterpret_cast<uint16_t*>(w); w += round_up((size_t)r * r * 2, 256);
+                M.gramQ = reinterpret_cast<uint16_t*>(w); w += round_up((size_t)r * r * 2, 256);
+                M.grampart = reinterpret_cast<float*>(w);
+                w += round_up((size_t)std::max(M.gchunks_m, M.gchunks_n) * r * r * 4, 256);
+            }
             if (kind == kKindTransfer) {
                 M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256);
                 if (r >= 64) { M.rowpart = reinterpret_cast<float*>(w); w += round_up((size_t)M.ncolchunks * r * r * 4, 256); }
@@ -1027,10 +1111,27 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16,
         if (st != FLORA_OK) return st;
     } else {
         DecompressParams dp{u->alpha, u->lr, u->beta2, u->eps1, wpolicy};
-        if (factored) {
+        const int gram = (factored && p->gram) ? 1 : 0;
+        if (gram) {
+            // row and column sums of Gt^2 as quadratic forms in A^T A and S^T S, then the clipping
+            // sum as one in A^T diag(1 / K) A: no pass over the n x m product before the update
+            const WorkItem* gm = p->d_items2;
+            const WorkItem* gn = gm + p->n_gm;
+            const WorkItem* qr = gn + p->n_gn;
+            const WorkItem* qc = qr + p->n_qr;
+            FLORA_HIP(launch_gram(dm, gm, p->n_gm, count, sa, r, 0, s));
+            FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 0, u->alpha, s));
+            FLORA_HIP(launch_gram(dm, gn, p->n_gn, count, sa, r, 2, s));
+            FLORA_HIP(launch_quadform(dm, qc, p->n_qc, sa, r, 1, u->alpha, s));
+            FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, 1, s));
+            if (u->clip_d > 0.f) {
+                FLORA_HIP(launch_gram(dm, gm, p->n_gm, count, sa, r, 1, s));
+                FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 2, u->alpha, s));
+            }
+        } else if (factored) {
             st = run_decompress(p, sa, r, kModeStats, 0, dp, s);
             if (st != FLORA_OK) return st;
-            FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, s));
+            FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, 0, s));
             if (u->clip_d > 0.f) {
                 st = run_decompress(p, sa, r, kModeRms, 0, dp, s);
                 if (st != FLORA_OK) return st;
@@ -1040,7 +1141,7 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16,
             if (st != FLORA_OK) return st;
         }
         // clip factor from the partial sums of U^2; parameter scale from the caller's sum of W^2
-        FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, scaled ? 1 : 0, u->eps2, s));
+        FLORA_HIP(launch_rms_finalize(dm, count, u->clip_d, scaled ? 1 : 0, u->eps2, gram, s));
         st = run_decompress(p, sa, r, factored ? kModeFactored : kModeFull2, wbf16, dp, s);
         if (st != FLORA_OK) return st;
         // the update pass left per-workgroup sums of the new W^2
@@ -1451,6 +1552,12 @@ int flora_set_tuning(const char* name, int value)
     } else if (std::strcmp(name, "update_wpolicy") == 0) {
         if (value < 0 || value > 4) return FLORA_ERR_INVALID;
         g_tune.update_wpolicy = value;
+    } else if (std::strcmp(name, "gram_chunk") == 0) {
+        if (value < 0 || (value % 64) != 0) return FLORA_ERR_INVALID;
+        g_tune.gram_chunk = value;
+    } else if (std::strcmp(name, "factored_gram") == 0) {
+        if (value < 0 || value > 2) return FLORA_ERR_INVALID;
+        g_tune.factored_gram = value;
     } else if (std::strcmp(name, "decompress_rows") == 0) {
         if (value < 0 || (value % 32) != 0) return FLORA_ERR_INVALID;
         g_tune.decompress_rows = value;

@@ -452,6 +452,14 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     // ---- shared columns: count arrivals; the last one combines.  The partials are stored and
     // loaded with device scope on the accesses themselves (write-through / L2-bypassing), so
     // no cache-wide release or acquire is needed: a store is visible once it has completed.
+    // This is the release / acquire pair of the gfx942/gfx950 memory model spelled out for the
+    // few accesses that need it: a device-scope release is "write dirty lines through, wait for
+    // the stores" and a device-scope acquire is "do not read stale non-coherent lines".  A
+    // release fence would write back the whole L2 of this XCD, which holds megabytes of state
+    // the launch has just written (measured: tens of microseconds per fence); here only the
+    // partial products are written through, the wait below (vmcnt(0), then the barrier) orders
+    // them before the arrival count, the count is a device-scope atomic, and the last arriver's
+    // loads carry the scope bit that makes them miss lines another XCD may have written.
     __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0): this thread's partial stores have completed ...
     __syncthreads();                          // ... and so have everybody's, before the arrival is counted
     if (tid == 0) lds_flag = atomicAdd(counters + it.cidx, 1u);

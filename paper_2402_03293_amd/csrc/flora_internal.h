@@ -20,10 +20,15 @@ struct MatDev {
     float* colpart;     // [nrowblocks][m] partial column sums of Gt^2 (workspace)
     float* itempart;    // [nitems] per-workgroup partial sums of U^2, later of the new W^2 (workspace)
     float* scal;        // [4]: mean(R), clip scale, parameter scale max(eps2, RMS(W)) or 1, spare (workspace)
+    uint16_t* gramP;    // r x r bf16: A^T A, later A^T diag(1/K) A (factored rule through Gram matrices; workspace)
+    uint16_t* gramQ;    // r x r bf16: S^T S (workspace)
+    float* grampart;    // [chunks][r][r] partial Gram matrices of the chunks of m or of n (workspace)
     long long n, m;
     uint32_t seed_lo, seed_hi, seedn_lo, seedn_hi;   // used by the transfer kernels only
     int ncolchunks, nrowblocks;   // decompress tiling of this matrix
-    int item0, nitems;            // number of decompress workgroups of this matrix (item0: unused)
+    int item0, nitems;            // nitems: decompress workgroups of this matrix; item0: row blocks of the
+                                  // quadratic-form pass (its partial sums of U^2 are itempart[0 .. item0))
+    int gchunks_m, gchunks_n;     // chunks of the Gram sums over m and over n
 };
 
 // Seeds of the matrices of one grouped launch, passed by value as a kernel argument:
@@ -240,9 +245,13 @@ hipError_t launch_decompress_bf16(const MatDev* mats, const WorkItem* items, int
 hipError_t launch_transfer_T(const MatDev* mats, const WorkItem* items, int nitems, int count, int r, hipStream_t s);
 hipError_t launch_apply_T(const MatDev* mats, const WorkItem* items, int nitems, int r, float ca, float cb,
                           hipStream_t s);
-hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s);
-hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
+hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, int gram, hipStream_t s);
+hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2, int gram,
                                hipStream_t s);
+hipError_t launch_gram(const MatDev* mats, const WorkItem* items, int nitems, int count, const SeedArgs& seeds, int r,
+                       int src, hipStream_t s);
+hipError_t launch_quadform(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int r, int out,
+                           float alpha, hipStream_t s);
 hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s);
 hipError_t launch_weight_sumsq(const MatDev* mats, int count, int weight_is_bf16, float* partials, hipStream_t s);
 hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s);
@@ -257,5 +266,7 @@ constexpr int kApplyTRows = 32;          // rows per workgroup, state <- state T
 constexpr int kApplyTRowsBig = 64;       // ... ranks 64 and above
 constexpr int kTransferChunk = 1024;     // columns per workgroup of the T kernel, ranks 64 and above
 constexpr int kSumsqBlocks = 256;        // workgroups per matrix, sum of W^2
+constexpr int kGramChunk = 3072;         // long-index entries per workgroup of the Gram sums
+constexpr int kQuadformRows = 1024;      // rows of Z per workgroup of the quadratic forms
 
 }  // namespace flora

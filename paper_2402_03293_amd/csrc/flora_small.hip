@@ -25,24 +25,26 @@ __device__ __forceinline__ float block_sum_256(float v, float* lds)
 
 // R_i <- beta2 R_i + (1 - beta2) (rowmean(Gt^2) + eps1), K_j likewise by column,
 // scal[0] <- mean(R), scal[1] <- 1 (no clipping until rms_finalize says otherwise).
+// (gram: the sums came whole from the quadratic-form kernels, one value per row and column)
 __global__ __launch_bounds__(256) void stats_finalize_kernel(const MatDev* __restrict__ mats,
-                                                             float beta2, float eps1)
+                                                             float beta2, float eps1, int gram)
 {
     __shared__ float lds[256];
     const MatDev& M = mats[blockIdx.x];
     const long long n = M.n, m = M.m;
     const int tid = threadIdx.x;
+    const int ncc = gram ? 1 : M.ncolchunks, nrb = gram ? 1 : M.nrowblocks;
     float rsum = 0.f;
     for (long long i = tid; i < n; i += 256) {
         float s = 0.f;
-        for (int c = 0; c < M.ncolchunks; ++c) s += M.rowpart[(long long)c * n + i];
+        for (int c = 0; c < ncc; ++c) s += M.rowpart[(long long)c * n + i];
         const float r = beta2 * M.row_stat[i] + (1.f - beta2) * (s / (float)m + eps1);
         M.row_stat[i] = r;
         rsum += r;
     }
     for (long long j = tid; j < m; j += 256) {
         float s = 0.f;
-        for (int b = 0; b < M.nrowblocks; ++b) s += M.colpart[(long long)b * m + j];
+        for (int b = 0; b < nrb; ++b) s += M.colpart[(long long)b * m + j];
         M.col_stat[j] = beta2 * M.col_stat[j] + (1.f - beta2) * (s / (float)n + eps1);
     }
     const float tot = block_sum_256(rsum, lds);
@@ -55,8 +57,9 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const MatDev* __res
 // scal[1] <- 1 / max(1, RMS(U) / clip_d), RMS(U)^2 = sum of the workgroup partials / (n m)
 // (1 when clip_d == 0: no clipping);  scal[2] <- max(eps2, RMS(W)) from the caller's sum of W^2
 // when the step is relative to the parameter scale, else 1.
+// (gram: the partial sums of U^2 are those of the quadratic-form pass, one per row block)
 __global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restrict__ mats, float clip_d,
-                                                           int scale_parameter, float eps2)
+                                                           int scale_parameter, float eps2, int gram)
 {
     __shared__ float lds[256];
     const MatDev& M = mats[blockIdx.x];
@@ -64,7 +67,8 @@ __global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restr
     float tot = 0.f;
     if (clip_d > 0.f) {
         float s = 0.f;
-        for (int i = tid; i < M.nitems; i += 256) s += M.itempart[i];
+        const int np = gram ? M.item0 : M.nitems;
+        for (int i = tid; i < np; i += 256) s += M.itempart[i];
         tot = block_sum_256(s, lds);
     }
     if (tid == 0) {
@@ -151,19 +155,19 @@ __global__ __launch_bounds__(256) void zero_state_kernel(const MatDev* __restric
 
 }  // namespace
 
-hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, hipStream_t s)
+hipError_t launch_stats_finalize(const MatDev* mats, int count, float beta2, float eps1, int gram, hipStream_t s)
 {
     if (count == 0) return hipSuccess;
-    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, beta2, eps1);
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, beta2, eps1, gram);
     return hipGetLastError();
 }
 
-hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2,
+hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int scale_parameter, float eps2, int gram,
                                hipStream_t s)
 {
     if (count == 0) return hipSuccess;
     hipLaunchKernelGGL(rms_finalize_kernel, dim3((unsigned)count), dim3(256), 0, s, mats, clip_d,
-                       scale_parameter, eps2);
+                       scale_parameter, eps2, gram);
     return hipGetLastError();
 }
 

@@ -190,7 +190,7 @@ def test_workspace_bytes_is_the_sum_of_the_fused_steps_plans(index, r):
     assert total % 256 == 0 and total > 0
     # a plan = its work tables (48 bytes per workgroup) + its work area + 8 descriptor images
     items, info = flora.debug_work_items(1, shapes, r)
-    image = _round256(152 * len(shapes))
+    image = _round256(184 * len(shapes))
     assert flora.debug_plan_bytes(1, shapes, r) == _round256(48 * len(items)) + 8 * image
     gdt = flora.F32 if wl.grad_dtype == "f32" else flora.BF16
     items, info = flora.debug_work_items(0, shapes, r, gdt)

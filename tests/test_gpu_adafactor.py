@@ -382,3 +382,46 @@ def test_update_cache_policies_give_the_same_bits(n, m, r, wdt, rule):
         assert not torch.equal(W, W0)
     for W in out[1:]:
         assert torch.equal(W, out[0])
+
+
+# ------------------------------------------- the factored rule through Gram matrices
+# Row sums, column sums and the clipping sum of the rule as quadratic forms in A^T A, S^T S and
+# A^T diag(1/K) A (ranks >= 64), against the oracle, and against the passes over the decompressed
+# gradient that they replace: ragged shapes, several chunks of the Gram sums (m or n above 3072),
+# several row blocks of the quadratic forms (above 1024), grouped matrices, with and without clipping.
+@pytest.mark.parametrize("r", [64, 128, 256])
+@pytest.mark.parametrize("clip_d,beta2", [(1.0, 0.0), (0.0, 0.6), (0.3, 0.8)])
+def test_factored_rule_through_gram_matrices(r, clip_d, beta2):
+    shapes = [(300, 520), (130, 6500), (3300, 264), (64, 64), (1100, 1032)]
+    count = len(shapes)
+    g = torch.Generator(device="cpu").manual_seed(900 + r)
+    S = [torch.randn(n, r, generator=g).to(DEV) for n, _ in shapes]
+    W0 = [torch.randn(*s, generator=g).to(DEV) for s in shapes]
+    R0 = [(torch.rand(n, generator=g) + 0.5).to(DEV) for n, _ in shapes]
+    K0 = [(torch.rand(m, generator=g) + 0.5).to(DEV) for _, m in shapes]
+    seeds = [int(flora.derive_seed(77, l, r)) for l in range(count)]
+    lr, alpha, eps1 = 0.01, 0.5, 1e-30
+    res = {}
+    for mode in (1, 2):
+        W, R, K = [x.clone() for x in W0], [x.clone() for x in R0], [x.clone() for x in K0]
+        flora.set_tuning("factored_gram", mode)
+        try:
+            mats = flora.matrices(shapes, weights=W, states=S, row_stats=R, col_stats=K, seeds=seeds)
+            flora.apply_update(mats, r, flora.F32, flora.factored_update(lr, alpha, beta2, eps1, clip_d))
+            sync()
+        finally:
+            flora.set_tuning("factored_gram", 0)
+        res[mode] = (W, R, K)
+    for l, (n, m) in enumerate(shapes):
+        Gt = oracle.decompress(to64(S[l]), m, seeds[l], alpha=alpha)
+        Wr, Rr, Kr = oracle.factored_update(to64(W0[l]), Gt, to64(R0[l]), to64(K0[l]), beta2, eps1, clip_d, lr)
+        for mode in (1, 2):
+            W, R, K = res[mode]
+            assert rel_fro(to64(R[l]), Rr) < TOL_BF16, (mode, shapes[l])
+            assert rel_fro(to64(K[l]), Kr) < TOL_BF16, (mode, shapes[l])
+            assert rel_fro(to64(W[l]) - to64(W0[l]), Wr - to64(W0[l])) < TOL_BF16, (mode, shapes[l])
+        # the two routes agree far more closely with each other than either must with the oracle
+        assert rel_fro(to64(res[2][1][l]), to64(res[1][1][l])) < 2e-3
+        assert rel_fro(to64(res[2][2][l]), to64(res[1][2][l])) < 2e-3
+        e = rel_fro(to64(res[2][1][l]), Rr)
+        print("gram route r=%d %s: R err %.2e K err %.2e" % (r, shapes[l], e, rel_fro(to64(res[2][2][l]), Kr)))

@@ -330,11 +330,14 @@ def test_workload4_accumulate_and_factored_update():
     for l in range(count):
         assert float(C[l].abs().max()) == 0.0
         assert bool(torch.isfinite(R[l]).all()) and bool(torch.isfinite(K[l]).all())
-    # properties that hold at any size: sum_i R_i * m == sum_j K_j * n (both are the total of Q)
+    # properties that hold at any size: sum_i R_i * m == sum_j K_j * n (both are the total of Q).
+    # The two sides are computed independently (row sums through A^T A, column sums through S^T S,
+    # each Gram matrix rounded to bf16 once), so they agree to that rounding averaged over the r
+    # diagonal entries that carry the trace, about 2^-9 / sqrt(r), not to fp32 summation order
     for l in (100, 250, 383):
         n, m = wl.shapes[l]
         a, b = float(R[l].double().sum()) * m, float(K[l].double().sum()) * n
-        assert abs(a - b) <= 1e-4 * abs(a)
+        assert abs(a - b) <= 1e-3 * abs(a)
 
 
 @pytest.mark.parametrize("rule", ["adafactor", "unfactored"])

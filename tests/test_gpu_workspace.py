@@ -182,3 +182,26 @@ def test_no_device_allocation_with_a_workspace():
     torch.cuda.synchronize()
     free_after, _ = torch.cuda.mem_get_info()
     assert free_after < free_before
+
+
+def test_more_matrices_than_one_launch_takes_with_a_workspace():
+    """A call over more matrices than one grouped launch carries seeds for (448) is split into
+    chunks; with a workspace every chunk's plan is resident for the call."""
+    r, count = 16, 460
+    shapes = [(32 + (l % 3) * 16, 64 + (l % 5) * 32) for l in range(count)]
+    g = torch.Generator(device="cpu").manual_seed(3)
+    G = [torch.randn(*s, generator=g).to(DEV) for s in shapes]
+    seeds = [int(flora.derive_seed(8, l, 0)) for l in range(count)]
+    need = flora.workspace_bytes(flora.matrices(shapes), r)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = {}
+    for mode in ("library", "workspace"):
+        flora.set_workspace(ws if mode == "workspace" else None)
+        S = [torch.zeros(n, r, device=DEV) for n, _ in shapes]
+        flora.compress(flora.matrices(shapes, grads=G, states=S, seeds=seeds), r, flora.F32)
+        torch.cuda.synchronize()
+        out[mode] = S
+    for l in range(count):
+        assert torch.equal(out["library"][l], out["workspace"][l])
+    for l in (0, 447, 448, 459):
+        assert rel_fro(to64(out["workspace"][l]), oracle.compress(to64(G[l]), r, seeds[l])) < tol_for(r)
