@@ -540,8 +540,8 @@ size_t workspace_bytes_for(const std::vector<MatDev>& mats, int kind, int r, boo
     size_t b = 0;
     for (const MatDev& M : mats) {
         if (kind == kKindFactored && gram) {
-            b += 2 * round_up((size_t)r * r * 2, 256);
-            b += round_up((size_t)std::max(M.gchunks_m, M.gchunks_n) * r * r * 4, 256);
+            b += 3 * round_up((size_t)r * r * 2, 256);
+            b += round_up((size_t)(2 * M.gchunks_m + M.gchunks_n) * r * r * 4, 256);
         }
         if (kind == kKindTransfer) {
             b += round_up((size_t)r * r * 4, 256);
@@ -755,9 +755,9 @@ int get_plan(int kind, int variant, int r, const std::vector<MatDev>& mats, hipS
             M.gchunks_m = t.gchunks_m; M.gchunks_n = t.gchunks_n;
             if (kind == kKindFactored && p->gram) {
                 M.gramP = reinterpret_cast<uint16_t*>(w); w += round_up((size_t)r * r * 2, 256);
-                M.gramQ = reinterpret_cast<uint16_t*>(w); w += round_up((size_t)r * r * 2, 256);
+                M.gramQ = reinterpret_cast<uint16_t*>(w); w += 2 * round_up((size_t)r * r * 2, 256);   // Q, then P'
                 M.grampart = reinterpret_cast<float*>(w);
-                w += round_up((size_t)std::max(M.gchunks_m, M.gchunks_n) * r * r * 4, 256);
+                w += round_up((size_t)(2 * M.gchunks_m + M.gchunks_n) * r * r * 4, 256);
             }
             if (kind == kKindTransfer) {
                 M.T = reinterpret_cast<float*>(w); w += round_up((size_t)r * r * 4, 256);
@@ -1119,15 +1119,14 @@ static int update_chunk(const flora_matrix_t* mats, int count, int r, int wbf16,
             const WorkItem* gn = gm + p->n_gm;
             const WorkItem* qr = gn + p->n_gn;
             const WorkItem* qc = qr + p->n_qr;
-            FLORA_HIP(launch_gram(dm, gm, p->n_gm, count, sa, r, 0, s));
-            FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 0, u->alpha, s));
+            // K first (S^T S, then the column sums from regenerated rows of A), because the one further
+            // regeneration of A then yields both A^T A and A^T diag(1 / K) A
+            const bool clip = u->clip_d > 0.f;
             FLORA_HIP(launch_gram(dm, gn, p->n_gn, count, sa, r, 2, s));
-            FLORA_HIP(launch_quadform(dm, qc, p->n_qc, sa, r, 1, u->alpha, s));
-            FLORA_HIP(launch_stats_finalize(dm, count, u->beta2, u->eps1, 1, s));
-            if (u->clip_d > 0.f) {
-                FLORA_HIP(launch_gram(dm, gm, p->n_gm, count, sa, r, 1, s));
-                FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 2, u->alpha, s));
-            }
+            FLORA_HIP(launch_quadform(dm, qc, p->n_qc, sa, r, 1, u->alpha, u->beta2, u->eps1, s));
+            FLORA_HIP(launch_gram(dm, gm, p->n_gm, count, sa, r, clip ? 3 : 0, s));
+            FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 0, u->alpha, u->beta2, u->eps1, s));
+            if (clip) FLORA_HIP(launch_quadform(dm, qr, p->n_qr, sa, r, 2, u->alpha, u->beta2, u->eps1, s));
         } else if (factored) {
             st = run_decompress(p, sa, r, kModeStats, 0, dp, s);
             if (st != FLORA_OK) return st;

@@ -21,6 +21,8 @@
 //   contraction order over k1 is free, and it is chosen so that the same lane's operand
 //   registers hold exactly Z[i][16 c + 4 g + v]: q_i is then a dot product of registers the lane
 //   already has, summed over the four lanes that share a row.
+#include <type_traits>
+
 #include "flora_gen.hip.h"
 #include "flora_internal.h"
 
@@ -174,7 +176,9 @@ __global__ __launch_bounds__(512) void gram_kernel(const MatDev* __restrict__ ma
     }
 
     // partial of this chunk: D layout, lane holds column 16 ct + li and rows 4 g + v of each tile
-    float* part = M.grampart + (size_t)it.part * R * R;
+    // (partials: those of P over chunks of m, then those of Q over chunks of n, then those of P')
+    const int part0 = SRC == 0 ? 0 : (SRC == 2 ? M.gchunks_m : M.gchunks_m + M.gchunks_n);
+    float* part = M.grampart + (size_t)(part0 + it.part) * R * R;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -187,21 +191,184 @@ __global__ __launch_bounds__(512) void gram_kernel(const MatDev* __restrict__ ma
             }
 }
 
+// P = A^T A and P' = A^T diag(1 / K) A from ONE regeneration of A, at ranks >= 128.  The vector
+// ALU work of the generator is what these sums cost, so both are taken from the same tile: the
+// tile goes to LDS twice, plain and with its long-index entries scaled by 1 / K, and
+// P'[k1][k2] = sum_t X[t][k1] (X[t][k2] / K_t) takes one operand from each copy.
+// 16 waves, so that four share a SIMD and one wave's generator chains run in the shadow of the
+// others'; v_mfma_f32_32x32x16_bf16 tiles; only the tiles on or above the diagonal of the
+// symmetric results are computed (36 of 64 at r = 256), consecutive ones to a wave (they mostly
+// share an operand), every SIMD multiplying the same number of them; a tile off the diagonal is
+// also stored as its mirror image.  PAIR false: P alone (no clipping asked for).
+template <int R>
+struct UpperTiles {
+    static constexpr int NT = R / 32;                      // 32-wide tiles per dimension
+    static constexpr int COUNT = NT * (NT + 1) / 2;
+    // the idx-th tile (ti <= tj) in row-major order of the upper triangle
+    __device__ static void at(int idx, int& ti, int& tj)
+    {
+        int c = idx, row = 0;
+        while (c >= NT - row) { c -= NT - row; ++row; }
+        ti = row; tj = row + c;
+    }
+};
+
+template <int R, bool PAIR, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __restrict__ mats, const WorkItem* __restrict__ items,
+                                                         const SeedArgs seeds)
+{
+    static_assert(R >= 128, "ranks 128 and 256");
+    typedef UpperTiles<R> UT;
+    constexpr int TW = (UT::COUNT + WAVES - 1) / WAVES;   // tiles per wave
+    constexpr int OWNERS = UT::COUNT < WAVES ? UT::COUNT : WAVES;
+    constexpr int NC = PAIR ? 2 : 1;                       // copies of a tile: plain, scaled
+    constexpr size_t kTileBytes = sizeof(uint16_t) * 2 * NC * R * kGLd, kTurnBytes = sizeof(float) * OWNERS * 32 * 33;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kTileBytes > kTurnBytes ? kTileBytes : kTurnBytes];
+    uint16_t (*ldsX)[NC][R][kGLd] = reinterpret_cast<uint16_t (*)[NC][R][kGLd]>(lds_raw);   // [buffer][copy][k][t]
+
+    const WorkItem it = items[blockIdx.x];
+    const MatDev& M = mats[it.mat];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ln = lane & 31, g = lane >> 5;
+    const long long t0 = it.col0, t1 = it.col1;
+    const int ntiles = (int)((t1 - t0 + kGT - 1) / kGT);
+
+    // this wave's tiles of the results: numbers wave, wave + WAVES, ... of the upper triangle, which
+    // gives every SIMD (waves w, w + 4, ...) the same number of them
+    int ti[TW], tj[TW];
+    bool own[TW];
+#pragma unroll
+    for (int w = 0; w < TW; ++w) {
+        const int idx = wave + WAVES * w;
+        own[w] = idx < UT::COUNT;
+        ti[w] = tj[w] = 0;
+        if (own[w]) UT::at(idx, ti[w], tj[w]);
+        ti[w] = __builtin_amdgcn_readfirstlane(ti[w]);
+        tj[w] = __builtin_amdgcn_readfirstlane(tj[w]);
+    }
+
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
+    const float cgen = neg2_ln2_over(R);
+    constexpr int NQ = R / (4 * WAVES);               // quads per thread and tile
+    constexpr int JG = kGT / NQ;
+    const int gen_j = NQ * (tid % JG);
+    const uint32_t gen_q = (uint32_t)(tid / JG);
+    auto produce = [&](int buf, int tile) {
+        const long long j = t0 + (long long)tile * kGT + gen_j;
+        float wt[NQ];
+#pragma unroll
+        for (int e = 0; e < NQ; ++e) {
+            wt[e] = 1.f;
+            if (PAIR) wt[e] = ldg(M.col_stat + ((j + e < t1) ? j + e : t1 - 1));
+        }
+        uint32_t pk[NC][NQ / 2][4];
+#pragma unroll
+        for (int e = 0; e < NQ; e += 2) {
+            const Quad z0 = normal_quad(seed_lo, seed_hi, (uint64_t)(j + e), gen_q, cgen);
+            const Quad z1 = normal_quad(seed_lo, seed_hi, (uint64_t)(j + e + 1), gen_q, cgen);
+            const float m0 = (j + e < t1) ? 1.f : 0.f, m1 = (j + e + 1 < t1) ? 1.f : 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pk[0][e / 2][i] = pack_bf16x2(m0 * z0.z[i], m1 * z1.z[i]);
+            if (PAIR) {
+                const float w0 = m0 * __builtin_amdgcn_rcpf(wt[e]), w1 = m1 * __builtin_amdgcn_rcpf(wt[e + 1]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pk[NC - 1][e / 2][i] = pack_bf16x2(w0 * z0.z[i], w1 * z1.z[i]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint16_t* dst = &ldsX[buf][c][4 * gen_q + i][gen_j];
+                if (NQ == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(pk[c][0][i], pk[c][NQ / 8][i], pk[c][NQ / 4][i], pk[c][NQ / 2 - 1][i]);
+                else if (NQ == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(pk[c][0][i], pk[c][NQ / 2 - 1][i]);
+                else *reinterpret_cast<uint32_t*>(dst) = pk[c][0][i];
+            }
+    };
+
+    f32x16 acc[NC][TW];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int w = 0; w < TW; ++w)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][w][v] = 0.f;
+
+    // the waves of a SIMD (w, w + 4, ...) take producing the next tile and multiplying the current
+    // one in alternating orders
+    const bool produce_first = ((wave >> 2) & 1) == 0;
+    produce(0, 0);
+    __syncthreads();
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int buf = tile & 1;
+        if (produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
+        // Straight-line code over all TW slots (a wave that owns TW - 1 tiles multiplies tile (0, 0)
+        // again in its last slot and drops the result), so that the LDS reads of several
+        // matrix-core instructions are in flight together.
+#pragma unroll
+        for (int s = 0; s < kGT / 16; ++s) {
+#pragma unroll
+            for (int w = 0; w < TW; ++w) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8*>(&ldsX[buf][0][32 * ti[w] + ln][16 * s + 8 * g]);
+                const bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsX[buf][0][32 * tj[w] + ln][16 * s + 8 * g]);
+                acc[0][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0][w], 0, 0, 0);
+                if (PAIR) {
+                    const bf16x8 bs = *reinterpret_cast<const bf16x8*>(&ldsX[buf][NC - 1][32 * tj[w] + ln][16 * s + 8 * g]);
+                    acc[NC - 1][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bs, acc[NC - 1][w], 0, 0, 0);
+                }
+            }
+        }
+        if (!produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
+        __syncthreads();
+    }
+
+    // D layout of a 32 x 32 tile: lane holds column ln and rows 8 (v / 4) + 4 g + v % 4.  A tile off
+    // the diagonal is also stored as its mirror image, turned round in a piece of LDS that belongs
+    // to the wave alone (the tiles of X are done with), so that both stores write whole lines.
+    float* turn = reinterpret_cast<float*>(lds_raw) + wave * (32 * 33);     // (only waves that own tiles touch it)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        float* part = M.grampart + (size_t)((c ? M.gchunks_m + M.gchunks_n : 0) + it.part) * R * R;
+#pragma unroll
+        for (int w = 0; w < TW; ++w) {
+            if (own[w]) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k1 = 8 * (v / 4) + 4 * g + (v % 4);
+                    stg(part + (32 * ti[w] + k1) * R + 32 * tj[w] + ln, acc[c][w][v]);
+                    if (ti[w] != tj[w]) turn[ln * 33 + k1] = acc[c][w][v];
+                }
+                if (ti[w] != tj[w]) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int k2 = 2 * v + g;                       // row of the mirror image; ln runs along it
+                        stg(part + (32 * tj[w] + k2) * R + 32 * ti[w] + ln, turn[k2 * 33 + ln]);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // B <- sum over the chunks of their partials, in chunk order; stored as bf16 with the columns of
-// every 32-block in the order quadform_kernel contracts them.  which 0: P (chunks of m), 1: Q (chunks of n)
+// every 32-block in the order quadform_kernel contracts them.  which 0: P (chunks of m), 1: Q (chunks
+// of n), 2: P' (chunks of m; it is kept right behind Q)
 template <int R>
 __global__ __launch_bounds__(256) void combine_gram_kernel(const MatDev* __restrict__ mats, int which)
 {
     const MatDev& M = mats[blockIdx.y];
     const int idx = (blockIdx.x * 256 + threadIdx.x) * 4;       // four consecutive k1 of one row k2
     if (idx >= R * R) return;
-    const int nch = which ? M.gchunks_n : M.gchunks_m;
+    const int nch = which == 1 ? M.gchunks_n : M.gchunks_m;
+    const int part0 = which == 0 ? 0 : (which == 1 ? M.gchunks_m : M.gchunks_m + M.gchunks_n);
     v4f s = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < nch; ++c) {
-        const v4f p = ldg4(M.grampart + (size_t)c * R * R + idx);
+        const v4f p = ldg4(M.grampart + (size_t)(part0 + c) * R * R + idx);
         s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
     }
-    uint16_t* B = which ? M.gramQ : M.gramP;
+    uint16_t* B = which == 0 ? M.gramP : (which == 1 ? M.gramQ : M.gramQ + R * R);
     const int k2 = idx / R, k1 = idx % R;                       // k1 % 4 == 0: the four stay together
     const int pos = (k1 & ~31) + perm32(k1 & 31);
     const v2u pk = {pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w)};
@@ -209,18 +376,22 @@ __global__ __launch_bounds__(256) void combine_gram_kernel(const MatDev* __restr
 }
 
 // SRC 0: Z = S (rows of the state), B = P;  SRC 1: Z = A(seed) (rows = columns of W), B = Q.
-// OUT 0: rowpart[i] <- alpha^2 q_i;  OUT 1: colpart[j] <- alpha^2 q_j;
-// OUT 2: itempart[block] <- alpha^2 mean(R) sum_i q_i / R_i  (the clipping sum of this row block)
-template <int R, int SRC, int OUT>
-__global__ __launch_bounds__(512) void quadform_kernel(const MatDev* __restrict__ mats, const WorkItem* __restrict__ items,
-                                                       const SeedArgs seeds, float alpha)
+// The statistics are finished where the sums appear (each row and column belongs to one lane):
+// OUT 0: R_i <- beta2 R_i + (1 - beta2) (alpha^2 q_i / m + eps1), and rowpart[block] <- the block's sum
+//        of the new R_i (for mean(R));
+// OUT 1: K_j <- beta2 K_j + (1 - beta2) (alpha^2 q_j / n + eps1);
+// OUT 2: itempart[block] <- alpha^2 sum_i q_i / R_i  (the clipping sum of this row block, but for
+//        the factor mean(R), which rms_finalize_kernel supplies)
+template <int R, int SRC, int OUT, int WAVES, int ZT>
+__global__ __launch_bounds__(64 * WAVES) void quadform_kernel(const MatDev* __restrict__ mats, const WorkItem* __restrict__ items,
+                                                       const SeedArgs seeds, float alpha, float beta2, float eps1)
 {
     constexpr int S = R / 32;            // contraction steps
     constexpr int CT = R / 16;           // 16-row tiles of B
     constexpr int LDB = R + 8;           // padded LDS row (bf16 elements)
-    constexpr int ZT = 2;                // 16-row tiles of Z per wave and round
+    // (ZT: 16-row tiles of Z per wave and round)
     __shared__ __attribute__((aligned(16))) uint16_t ldsB[R][LDB];
-    __shared__ float lds_fin[8];
+    __shared__ float lds_fin[WAVES];
 
     const WorkItem it = items[blockIdx.x];
     const MatDev& M = mats[it.mat];
@@ -235,8 +406,8 @@ __global__ __launch_bounds__(512) void quadform_kernel(const MatDev* __restrict_
 
     // B into LDS: R rows of R bf16, 16 bytes per thread and step
     {
-        const uint16_t* B = SRC == 0 ? M.gramP : M.gramQ;
-        for (int f = tid; f < R * (R / 8); f += 512) {
+        const uint16_t* B = SRC == 1 ? M.gramQ : (OUT == 2 ? M.gramQ + R * R : M.gramP);
+        for (int f = tid; f < R * (R / 8); f += 64 * WAVES) {
             const int k2 = f / (R / 8), c8 = f % (R / 8);
             *reinterpret_cast<v4u*>(&ldsB[k2][8 * c8]) = ldg4(B + k2 * R + 8 * c8);
         }
@@ -244,7 +415,7 @@ __global__ __launch_bounds__(512) void quadform_kernel(const MatDev* __restrict_
     __syncthreads();
 
     float total = 0.f;
-    for (long long rb = it.row0; rb < row_end; rb += 8 * 16 * ZT) {
+    for (long long rb = it.row0; rb < row_end; rb += WAVES * 16 * ZT) {
         // this wave's rows: rb + wave * 16 ZT + 16 z + li
         bf16x8 zreg[ZT][S];
 #pragma unroll
@@ -309,13 +480,22 @@ __global__ __launch_bounds__(512) void quadform_kernel(const MatDev* __restrict_
             v += __shfl_xor(v, 32);             // all four lanes of row li now hold q_i
             const long long row = rb + (wave * ZT + z) * 16 + li;
             if (row < row_end) {
-                if (OUT == 0) { if (g == 0) stg(M.rowpart + row, alpha * alpha * v); }
-                else if (OUT == 1) { if (g == 0) stg(M.colpart + row, alpha * alpha * v); }
-                else if (g == 0) total += v / ldg(M.row_stat + row);
+                if (OUT == 0) {
+                    if (g == 0) {
+                        const float rn = beta2 * ldg(M.row_stat + row) + (1.f - beta2) * (alpha * alpha * v / (float)M.m + eps1);
+                        stg(M.row_stat + row, rn);
+                        total += rn;
+                    }
+                } else if (OUT == 1) {
+                    if (g == 0)
+                        stg(M.col_stat + row, beta2 * ldg(M.col_stat + row) + (1.f - beta2) * (alpha * alpha * v / (float)M.n + eps1));
+                } else if (g == 0) {
+                    total += v / ldg(M.row_stat + row);
+                }
             }
         }
     }
-    if (OUT == 2) {
+    if (OUT != 1) {
         float t = total;
         t += __shfl_xor(t, 8);
         t += __shfl_xor(t, 4);
@@ -323,35 +503,50 @@ __global__ __launch_bounds__(512) void quadform_kernel(const MatDev* __restrict_
         t += __shfl_xor(t, 1);
         if (lane == 0) lds_fin[wave] = t;
         __syncthreads();
-        if (tid == 0)
-            M.itempart[it.part] = alpha * alpha * ldg(M.scal) *
-                                  (((lds_fin[0] + lds_fin[1]) + (lds_fin[2] + lds_fin[3])) +
-                                   ((lds_fin[4] + lds_fin[5]) + (lds_fin[6] + lds_fin[7])));
+        if (tid == 0) {
+            float fin = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) fin += lds_fin[w];
+            if (OUT == 0) M.rowpart[it.part] = fin;
+            else M.itempart[it.part] = alpha * alpha * fin;
+        }
     }
 }
 
 template <int R>
-hipError_t launch_gram_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int src, hipStream_t s)
+hipError_t launch_gram_r(const MatDev* mats, const WorkItem* items, int nitems, int count, const SeedArgs& seeds, int src,
+                         hipStream_t s)
 {
-    const dim3 grid((unsigned)nitems), block(512);
-    switch (src) {
-    case 0: hipLaunchKernelGGL((gram_kernel<R, 0>), grid, block, 0, s, mats, items, seeds); break;
-    case 1: hipLaunchKernelGGL((gram_kernel<R, 1>), grid, block, 0, s, mats, items, seeds); break;
-    case 2: hipLaunchKernelGGL((gram_kernel<R, 2>), grid, block, 0, s, mats, items, seeds); break;
-    default: return hipErrorInvalidValue;
+    const dim3 grid((unsigned)nitems), block(512), cgrid((unsigned)(R * R / 1024), (unsigned)count);
+    bool p = false, q = false, p2 = false;               // which sums this launch produces
+    if constexpr (R >= 128) {
+        constexpr int PW = R >= 256 ? 8 : 16;           // waves that can hold both sets of accumulators
+        if (src == 0) { hipLaunchKernelGGL((gram_pair_kernel<R, false, 16>), grid, dim3(1024), 0, s, mats, items, seeds); p = true; }
+        if (src == 3) { hipLaunchKernelGGL((gram_pair_kernel<R, true, PW>), grid, dim3(64 * PW), 0, s, mats, items, seeds); p = p2 = true; }
+    } else {
+        if (src == 0 || src == 3) { hipLaunchKernelGGL((gram_kernel<R, 0>), grid, block, 0, s, mats, items, seeds); p = true; }
+        if (src == 3) { hipLaunchKernelGGL((gram_kernel<R, 1>), grid, block, 0, s, mats, items, seeds); p2 = true; }
     }
+    if (src == 2) { hipLaunchKernelGGL((gram_kernel<R, 2>), grid, block, 0, s, mats, items, seeds); q = true; }
+    if (!p && !q && !p2) return hipErrorInvalidValue;
+    if (p) hipLaunchKernelGGL((combine_gram_kernel<R>), cgrid, dim3(256), 0, s, mats, 0);
+    if (q) hipLaunchKernelGGL((combine_gram_kernel<R>), cgrid, dim3(256), 0, s, mats, 1);
+    if (p2) hipLaunchKernelGGL((combine_gram_kernel<R>), cgrid, dim3(256), 0, s, mats, 2);
     return hipGetLastError();
 }
 
 template <int R>
 hipError_t launch_quadform_r(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int out,
-                             float alpha, hipStream_t s)
+                             float alpha, float beta2, float eps1, hipStream_t s)
 {
-    const dim3 grid((unsigned)nitems), block(512);
+    // r = 256: the operand registers of a row tile are a quarter of a 128-register budget, so 16
+    // waves with one row tile each; below that 8 waves with two
+    constexpr int W = R >= 256 ? 16 : 8, ZT = R >= 256 ? 1 : 2;
+    const dim3 grid((unsigned)nitems), block(64 * W);
     switch (out) {
-    case 0: hipLaunchKernelGGL((quadform_kernel<R, 0, 0>), grid, block, 0, s, mats, items, seeds, alpha); break;
-    case 1: hipLaunchKernelGGL((quadform_kernel<R, 1, 1>), grid, block, 0, s, mats, items, seeds, alpha); break;
-    case 2: hipLaunchKernelGGL((quadform_kernel<R, 0, 2>), grid, block, 0, s, mats, items, seeds, alpha); break;
+    case 0: hipLaunchKernelGGL((quadform_kernel<R, 0, 0, W, ZT>), grid, block, 0, s, mats, items, seeds, alpha, beta2, eps1); break;
+    case 1: hipLaunchKernelGGL((quadform_kernel<R, 1, 1, W, ZT>), grid, block, 0, s, mats, items, seeds, alpha, beta2, eps1); break;
+    case 2: hipLaunchKernelGGL((quadform_kernel<R, 0, 2, W, ZT>), grid, block, 0, s, mats, items, seeds, alpha, beta2, eps1); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -359,44 +554,31 @@ hipError_t launch_quadform_r(const MatDev* mats, const WorkItem* items, int nite
 
 }  // namespace
 
-// src 0: P = A^T A, 1: P' = A^T diag(1 / K) A (both over chunks of m), 2: Q = S^T S (chunks of n);
-// partial sums per work item, then the chunks are added in order and stored as bf16
+// src 0: P = A^T A; 3: P and P' = A^T diag(1 / K) A from one regeneration of A (over chunks of m);
+// 2: Q = S^T S (chunks of n).  Partial sums per work item, then the chunks are added in order and
+// stored as bf16.
 hipError_t launch_gram(const MatDev* mats, const WorkItem* items, int nitems, int count, const SeedArgs& seeds, int r,
                        int src, hipStream_t s)
 {
     if (nitems == 0 || count == 0) return hipSuccess;
-    hipError_t e;
-    const dim3 cgrid((unsigned)(r * r / 1024), (unsigned)count);
     switch (r) {
-    case 64:
-        e = launch_gram_r<64>(mats, items, nitems, seeds, src, s);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((combine_gram_kernel<64>), cgrid, dim3(256), 0, s, mats, src == 2 ? 1 : 0);
-        break;
-    case 128:
-        e = launch_gram_r<128>(mats, items, nitems, seeds, src, s);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((combine_gram_kernel<128>), cgrid, dim3(256), 0, s, mats, src == 2 ? 1 : 0);
-        break;
-    case 256:
-        e = launch_gram_r<256>(mats, items, nitems, seeds, src, s);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((combine_gram_kernel<256>), cgrid, dim3(256), 0, s, mats, src == 2 ? 1 : 0);
-        break;
+    case 64: return launch_gram_r<64>(mats, items, nitems, count, seeds, src, s);
+    case 128: return launch_gram_r<128>(mats, items, nitems, count, seeds, src, s);
+    case 256: return launch_gram_r<256>(mats, items, nitems, count, seeds, src, s);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
-// out 0: row sums of Gt^2 (Z = S, B = P), 1: column sums (Z = A, B = Q), 2: the clipping sum (Z = S, B = P')
+// out 0: row sums of Gt^2 (Z = S, B = P) into the row statistics, 1: column sums (Z = A, B = Q) into the
+// column statistics, 2: the clipping sum (Z = S, B = P')
 hipError_t launch_quadform(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int r, int out,
-                           float alpha, hipStream_t s)
+                           float alpha, float beta2, float eps1, hipStream_t s)
 {
     if (nitems == 0) return hipSuccess;
     switch (r) {
-    case 64: return launch_quadform_r<64>(mats, items, nitems, seeds, out, alpha, s);
-    case 128: return launch_quadform_r<128>(mats, items, nitems, seeds, out, alpha, s);
-    case 256: return launch_quadform_r<256>(mats, items, nitems, seeds, out, alpha, s);
+    case 64: return launch_quadform_r<64>(mats, items, nitems, seeds, out, alpha, beta2, eps1, s);
+    case 128: return launch_quadform_r<128>(mats, items, nitems, seeds, out, alpha, beta2, eps1, s);
+    case 256: return launch_quadform_r<256>(mats, items, nitems, seeds, out, alpha, beta2, eps1, s);
     default: return hipErrorInvalidValue;
     }
 }

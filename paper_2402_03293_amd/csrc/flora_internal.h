@@ -251,7 +251,7 @@ hipError_t launch_rms_finalize(const MatDev* mats, int count, float clip_d, int 
 hipError_t launch_gram(const MatDev* mats, const WorkItem* items, int nitems, int count, const SeedArgs& seeds, int r,
                        int src, hipStream_t s);
 hipError_t launch_quadform(const MatDev* mats, const WorkItem* items, int nitems, const SeedArgs& seeds, int r, int out,
-                           float alpha, hipStream_t s);
+                           float alpha, float beta2, float eps1, hipStream_t s);
 hipError_t launch_wsumsq_finalize(const MatDev* mats, int count, hipStream_t s);
 hipError_t launch_weight_sumsq(const MatDev* mats, int count, int weight_is_bf16, float* partials, hipStream_t s);
 hipError_t launch_zero_state(const MatDev* mats, int count, int r, hipStream_t s);

@@ -25,7 +25,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* lds)
 
 // R_i <- beta2 R_i + (1 - beta2) (rowmean(Gt^2) + eps1), K_j likewise by column,
 // scal[0] <- mean(R), scal[1] <- 1 (no clipping until rms_finalize says otherwise).
-// (gram: the sums came whole from the quadratic-form kernels, one value per row and column)
+// (gram: the sums came whole, one value per row and column)
 __global__ __launch_bounds__(256) void stats_finalize_kernel(const MatDev* __restrict__ mats,
                                                              float beta2, float eps1, int gram)
 {
@@ -65,11 +65,20 @@ __global__ __launch_bounds__(256) void rms_finalize_kernel(const MatDev* __restr
     const MatDev& M = mats[blockIdx.x];
     const int tid = threadIdx.x;
     float tot = 0.f;
+    if (gram) {
+        // mean(R) from the row blocks' sums of the new R, which the quadratic-form pass left in rowpart
+        float s = 0.f;
+        for (int i = tid; i < M.item0; i += 256) s += M.rowpart[i];
+        const float mean_r = block_sum_256(s, lds) / (float)M.n;
+        __syncthreads();
+        if (tid == 0) { M.scal[0] = mean_r; M.scal[1] = 1.f; }
+        tot = mean_r;                                      // the factor the clipping partials still lack
+    }
     if (clip_d > 0.f) {
         float s = 0.f;
         const int np = gram ? M.item0 : M.nitems;
         for (int i = tid; i < np; i += 256) s += M.itempart[i];
-        tot = block_sum_256(s, lds);
+        tot = block_sum_256(s, lds) * (gram ? tot : 1.f);
     }
     if (tid == 0) {
         float clip = 1.f;
