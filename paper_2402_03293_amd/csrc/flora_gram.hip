@@ -199,7 +199,9 @@ __global__ __launch_bounds__(512) void gram_kernel(const MatDev* __restrict__ ma
 // others'; v_mfma_f32_32x32x16_bf16 tiles; only the tiles on or above the diagonal of the
 // symmetric results are computed (36 of 64 at r = 256), consecutive ones to a wave (they mostly
 // share an operand), every SIMD multiplying the same number of them; a tile off the diagonal is
-// also stored as its mirror image.  PAIR false: P alone (no clipping asked for).
+// also stored as its mirror image.
+// MODE 0: P alone (no clipping asked for); 1: P and P'; 2: Q = S^T S, the tiles being rows of the
+// state, fetched one tile ahead and rounded to bf16 on their way into LDS.
 template <int R>
 struct UpperTiles {
     static constexpr int NT = R / 32;                      // 32-wide tiles per dimension
@@ -213,14 +215,15 @@ struct UpperTiles {
     }
 };
 
-template <int R, bool PAIR, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __restrict__ mats, const WorkItem* __restrict__ items,
+template <int R, int MODE, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void gram_sym_kernel(const MatDev* __restrict__ mats, const WorkItem* __restrict__ items,
                                                          const SeedArgs seeds)
 {
     static_assert(R >= 128, "ranks 128 and 256");
     typedef UpperTiles<R> UT;
     constexpr int TW = (UT::COUNT + WAVES - 1) / WAVES;   // tiles per wave
     constexpr int OWNERS = UT::COUNT < WAVES ? UT::COUNT : WAVES;
+    constexpr bool PAIR = MODE == 1;
     constexpr int NC = PAIR ? 2 : 1;                       // copies of a tile: plain, scaled
     constexpr size_t kTileBytes = sizeof(uint16_t) * 2 * NC * R * kGLd, kTurnBytes = sizeof(float) * OWNERS * 32 * 33;
     __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kTileBytes > kTurnBytes ? kTileBytes : kTurnBytes];
@@ -288,6 +291,42 @@ __global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __r
             }
     };
 
+    // loaded X (MODE 2): unit = (pair of rows 2 p, 2 p + 1; four columns 4 k4 ..); eight consecutive
+    // lanes take eight row pairs (consecutive words of an LDS row), the lanes 8 apart the next
+    // columns (a whole 128-byte line per row); rows past the chunk read through a resource that
+    // ends there
+    constexpr int NU = (8 * R) / (64 * WAVES) > 0 ? (8 * R) / (64 * WAVES) : 1;
+    const long long chunk_rows = t1 - t0;
+    const rsrc_t srs = make_rsrc(M.state + (MODE == 2 ? t0 * R : 0),
+                                 chunk_rows * (long long)R * 4 < 0x7fffffffLL ? chunk_rows * R * 4 : 0x7fffffffLL);
+    auto fetch_loaded = [&](v4f (&st)[NU][2], int tile) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int flat = tid + 64 * WAVES * u;
+            const int rest = flat >> 3;
+            const int k4 = rest % (R / 4);
+            const int p = (rest / (R / 4)) * 8 + (flat & 7);
+            const long long ra = (long long)tile * kGT + 2 * p;       // relative to the chunk
+            const uint32_t off = (uint32_t)((ra * R + 4 * k4) * 4);
+            st[u][0] = (ra < chunk_rows) ? buf_load_f4(srs, off) : v4f{0.f, 0.f, 0.f, 0.f};
+            st[u][1] = (ra + 1 < chunk_rows) ? buf_load_f4(srs, off + (uint32_t)(R * 4)) : v4f{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    auto stash_loaded = [&](const v4f (&st)[NU][2], int buf) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int flat = tid + 64 * WAVES * u;
+            const int rest = flat >> 3;
+            const int k4 = rest % (R / 4);
+            const int p = (rest / (R / 4)) * 8 + (flat & 7);
+            const v4f a = st[u][0], b = st[u][1];
+            *reinterpret_cast<uint32_t*>(&ldsX[buf][0][4 * k4 + 0][2 * p]) = pack_bf16x2(a.x, b.x);
+            *reinterpret_cast<uint32_t*>(&ldsX[buf][0][4 * k4 + 1][2 * p]) = pack_bf16x2(a.y, b.y);
+            *reinterpret_cast<uint32_t*>(&ldsX[buf][0][4 * k4 + 2][2 * p]) = pack_bf16x2(a.z, b.z);
+            *reinterpret_cast<uint32_t*>(&ldsX[buf][0][4 * k4 + 3][2 * p]) = pack_bf16x2(a.w, b.w);
+        }
+    };
+
     f32x16 acc[NC][TW];
 #pragma unroll
     for (int c = 0; c < NC; ++c)
@@ -299,11 +338,18 @@ __global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __r
     // the waves of a SIMD (w, w + 4, ...) take producing the next tile and multiplying the current
     // one in alternating orders
     const bool produce_first = ((wave >> 2) & 1) == 0;
-    produce(0, 0);
+    v4f stage[NU][2];
+    if (MODE == 2) {
+        fetch_loaded(stage, 0);
+        stash_loaded(stage, 0);
+        if (ntiles > 1) fetch_loaded(stage, 1);
+    } else {
+        produce(0, 0);
+    }
     __syncthreads();
     for (int tile = 0; tile < ntiles; ++tile) {
         const int buf = tile & 1;
-        if (produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
+        if (MODE != 2 && produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
         // Straight-line code over all TW slots (a wave that owns TW - 1 tiles multiplies tile (0, 0)
         // again in its last slot and drops the result), so that the LDS reads of several
         // matrix-core instructions are in flight together.
@@ -320,7 +366,11 @@ __global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __r
                 }
             }
         }
-        if (!produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
+        if (MODE != 2 && !produce_first && tile + 1 < ntiles) produce(buf ^ 1, tile + 1);
+        if (MODE == 2 && tile + 1 < ntiles) {
+            stash_loaded(stage, buf ^ 1);                        // tile + 1, fetched a round ago
+            if (tile + 2 < ntiles) fetch_loaded(stage, tile + 2);
+        }
         __syncthreads();
     }
 
@@ -330,7 +380,9 @@ __global__ __launch_bounds__(64 * WAVES) void gram_pair_kernel(const MatDev* __r
     float* turn = reinterpret_cast<float*>(lds_raw) + wave * (32 * 33);     // (only waves that own tiles touch it)
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        float* part = M.grampart + (size_t)((c ? M.gchunks_m + M.gchunks_n : 0) + it.part) * R * R;
+        // (partials: those of P over chunks of m, then those of Q over chunks of n, then those of P')
+        const int part0 = MODE == 2 ? M.gchunks_m : (c ? M.gchunks_m + M.gchunks_n : 0);
+        float* part = M.grampart + (size_t)(part0 + it.part) * R * R;
 #pragma unroll
         for (int w = 0; w < TW; ++w) {
             if (own[w]) {
@@ -521,13 +573,14 @@ hipError_t launch_gram_r(const MatDev* mats, const WorkItem* items, int nitems, 
     bool p = false, q = false, p2 = false;               // which sums this launch produces
     if constexpr (R >= 128) {
         constexpr int PW = R >= 256 ? 8 : 16;           // waves that can hold both sets of accumulators
-        if (src == 0) { hipLaunchKernelGGL((gram_pair_kernel<R, false, 16>), grid, dim3(1024), 0, s, mats, items, seeds); p = true; }
-        if (src == 3) { hipLaunchKernelGGL((gram_pair_kernel<R, true, PW>), grid, dim3(64 * PW), 0, s, mats, items, seeds); p = p2 = true; }
+        if (src == 0) { hipLaunchKernelGGL((gram_sym_kernel<R, 0, 16>), grid, dim3(1024), 0, s, mats, items, seeds); p = true; }
+        if (src == 3) { hipLaunchKernelGGL((gram_sym_kernel<R, 1, PW>), grid, dim3(64 * PW), 0, s, mats, items, seeds); p = p2 = true; }
+        if (src == 2) { hipLaunchKernelGGL((gram_sym_kernel<R, 2, 16>), grid, dim3(1024), 0, s, mats, items, seeds); q = true; }
     } else {
         if (src == 0 || src == 3) { hipLaunchKernelGGL((gram_kernel<R, 0>), grid, block, 0, s, mats, items, seeds); p = true; }
         if (src == 3) { hipLaunchKernelGGL((gram_kernel<R, 1>), grid, block, 0, s, mats, items, seeds); p2 = true; }
+        if (src == 2) { hipLaunchKernelGGL((gram_kernel<R, 2>), grid, block, 0, s, mats, items, seeds); q = true; }
     }
-    if (src == 2) { hipLaunchKernelGGL((gram_kernel<R, 2>), grid, block, 0, s, mats, items, seeds); q = true; }
     if (!p && !q && !p2) return hipErrorInvalidValue;
     if (p) hipLaunchKernelGGL((combine_gram_kernel<R>), cgrid, dim3(256), 0, s, mats, 0);
     if (q) hipLaunchKernelGGL((combine_gram_kernel<R>), cgrid, dim3(256), 0, s, mats, 1);
