@@ -36,6 +36,9 @@ constexpr int kGLd = kGT + 8;    // padded LDS row (bf16 elements): 144 bytes
 // Position within a 32-block of the contraction index k1 = 32 s + x, x = 16 h + 4 g + v (h < 2, g < 4,
 // v < 4): lane group g holds, for step s, the eight values x = 4 g + v and x = 16 + 4 g + v.
 __device__ __forceinline__ int perm32(int x) { return 8 * ((x >> 2) & 3) + 4 * (x >> 4) + (x & 3); }
+// The same for quadform_cols_kernel (32 x 32 x 16 tiles): x = 8 a + 4 g + v (a < 4, g < 2, v < 4); lane half
+// g holds, for step 2 s + (a >> 1) of the contraction, the values x = 8 a + 4 g + v in elements 4 (a & 1) + v.
+__device__ __forceinline__ int perm32w(int x) { return 16 * (x >> 4) + 8 * ((x >> 2) & 1) + 4 * ((x >> 3) & 1) + (x & 3); }
 
 // SRC 0: X = A(seed), 1: X = A(seed) diag(1 / sqrt(K)), 2: X = S (the state, fp32 in memory)
 template <int R, int SRC>
@@ -422,7 +425,8 @@ __global__ __launch_bounds__(256) void combine_gram_kernel(const MatDev* __restr
     }
     uint16_t* B = which == 0 ? M.gramP : (which == 1 ? M.gramQ : M.gramQ + R * R);
     const int k2 = idx / R, k1 = idx % R;                       // k1 % 4 == 0: the four stay together
-    const int pos = (k1 & ~31) + perm32(k1 & 31);
+    // (Q at ranks >= 128 is read by quadform_cols_kernel, everything else by quadform_kernel)
+    const int pos = (k1 & ~31) + ((which == 1 && R >= 128) ? perm32w(k1 & 31) : perm32(k1 & 31));
     const v2u pk = {pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w)};
     *reinterpret_cast<FLORA_GLOBAL v2u*>((FLORA_GLOBAL uint16_t*)(B + k2 * R + pos)) = pk;
 }
@@ -565,6 +569,86 @@ __global__ __launch_bounds__(64 * WAVES) void quadform_kernel(const MatDev* __re
     }
 }
 
+// The column statistics at ranks >= 128: K_j <- beta2 K_j + (1 - beta2) (alpha^2 A_j Q A_j^T / n + eps1),
+// rows A_j regenerated straight into matrix-core operand registers, Q in LDS.  The scheme of
+// quadform_kernel on v_mfma_f32_32x32x16_bf16: a wave owns 32 rows per round, D[k2][j] =
+// sum_k1 Q[k2][k1] A[j][k1] comes out with lane (j, g) holding k2 = 32 c + 8 a + 4 g + v, and the
+// contraction order is chosen (perm32w) so that the lane's own operand registers hold exactly
+// A[j][32 c + 8 a + 4 g + v].  Twice the rows per LDS read of Q and the faster tile shape.
+template <int R, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void quadform_cols_kernel(const MatDev* __restrict__ mats,
+                                                                   const WorkItem* __restrict__ items, const SeedArgs seeds,
+                                                                   float alpha, float beta2, float eps1)
+{
+    constexpr int S = R / 16;            // contraction steps
+    constexpr int CT = R / 32;           // 32-row tiles of Q
+    constexpr int LDB = R + 8;           // padded LDS row (bf16 elements)
+    __shared__ __attribute__((aligned(16))) uint16_t ldsB[R][LDB];
+
+    const WorkItem it = items[blockIdx.x];
+    const MatDev& M = mats[it.mat];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ln = lane & 31, g = lane >> 5;
+    const long long zn = M.m;
+    const long long row_end = ((long long)it.row0 + it.rows < zn) ? (long long)it.row0 + it.rows : zn;
+    const uint32_t seed_lo = seeds.s[it.mat].x, seed_hi = seeds.s[it.mat].y;
+    const float cgen = neg2_ln2_over(R);
+
+    for (int f = tid; f < R * (R / 8); f += 64 * WAVES) {
+        const int k2 = f / (R / 8), c8 = f % (R / 8);
+        *reinterpret_cast<v4u*>(&ldsB[k2][8 * c8]) = ldg4(M.gramQ + k2 * R + 8 * c8);
+    }
+    __syncthreads();
+
+    for (long long rb = it.row0; rb < row_end; rb += WAVES * 32) {
+        const long long row = rb + wave * 32 + ln;
+        const bool ok = row < row_end;
+        // (all lanes generate: rows past the end take the last row's values and are masked below)
+        const long long jr = ok ? row : zn - 1;
+        const float w = ok ? 1.f : 0.f;
+        bf16x8 zreg[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            // step s = 2 beta + sl holds k1 = 32 beta + 16 sl + 4 g + (0..3) and the same + 8: quads 8 beta + 4 sl + g and + 2
+            const uint32_t q0 = (uint32_t)(8 * (s >> 1) + 4 * (s & 1) + g);
+            const Quad a = normal_quad(seed_lo, seed_hi, (uint64_t)jr, q0, cgen);
+            const Quad b = normal_quad(seed_lo, seed_hi, (uint64_t)jr, q0 + 2u, cgen);
+            const v4u pk = {pack_bf16x2(w * a.z[0], w * a.z[1]), pack_bf16x2(w * a.z[2], w * a.z[3]),
+                            pack_bf16x2(w * b.z[0], w * b.z[1]), pack_bf16x2(w * b.z[2], w * b.z[3])};
+            zreg[s] = __builtin_bit_cast(bf16x8, pk);
+        }
+        float q = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const bf16x8 bv = *reinterpret_cast<const bf16x8*>(&ldsB[32 * c + ln][16 * s + 8 * g]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, zreg[s], acc, 0, 0, 0);
+            }
+            // acc[4 a + v] = D[32 c + 8 a + 4 g + v][j]; A[j][that k2] is element 4 (a & 1) + v of step 2 c + (a >> 1)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const v4u zz = __builtin_bit_cast(v4u, zreg[2 * c + (a >> 1)]);
+                const uint32_t w0 = (a & 1) ? zz.z : zz.x, w1 = (a & 1) ? zz.w : zz.y;
+                q = __builtin_fmaf(acc[4 * a + 0], __uint_as_float(w0 << 16), q);
+                q = __builtin_fmaf(acc[4 * a + 1], __uint_as_float(w0 & 0xffff0000u), q);
+                q = __builtin_fmaf(acc[4 * a + 2], __uint_as_float(w1 << 16), q);
+                q = __builtin_fmaf(acc[4 * a + 3], __uint_as_float(w1 & 0xffff0000u), q);
+            }
+            // (keeps the compiler from hoisting every tile's LDS reads to the top)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        q += __shfl_xor(q, 32);                 // both lanes of row j now hold A_j Q A_j^T
+        if (ok && g == 0)
+            stg(M.col_stat + row, beta2 * ldg(M.col_stat + row) + (1.f - beta2) * (alpha * alpha * q / (float)M.n + eps1));
+    }
+}
+
 template <int R>
 hipError_t launch_gram_r(const MatDev* mats, const WorkItem* items, int nitems, int count, const SeedArgs& seeds, int src,
                          hipStream_t s)
@@ -596,6 +680,12 @@ hipError_t launch_quadform_r(const MatDev* mats, const WorkItem* items, int nite
     // waves with one row tile each; below that 8 waves with two
     constexpr int W = R >= 256 ? 16 : 8, ZT = R >= 256 ? 1 : 2;
     const dim3 grid((unsigned)nitems), block(64 * W);
+    if constexpr (R >= 128) {
+        if (out == 1) {
+            hipLaunchKernelGGL((quadform_cols_kernel<R, 16>), grid, dim3(1024), 0, s, mats, items, seeds, alpha, beta2, eps1);
+            return hipGetLastError();
+        }
+    }
     switch (out) {
     case 0: hipLaunchKernelGGL((quadform_kernel<R, 0, 0, W, ZT>), grid, block, 0, s, mats, items, seeds, alpha, beta2, eps1); break;
     case 1: hipLaunchKernelGGL((quadform_kernel<R, 1, 1, W, ZT>), grid, block, 0, s, mats, items, seeds, alpha, beta2, eps1); break;
