@@ -278,20 +278,59 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     long long valid = row_end - wave_row0;
     valid = valid < 0 ? 0 : (valid > WR ? WR : valid);
     const rsrc_t rs = make_rsrc(G + (wave_row0 < n ? wave_row0 : 0) * m, valid * m * 2);
-    uint32_t lane_off[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) lane_off[rt] = ((uint32_t)(16 * rt + li) * (uint32_t)m + 8u * (uint32_t)g) * 2u;
-
     // Chunk (s, g) of a tile holds columns j0 + 32 s + 8 g .. + 7; m % 8 == 0, so a chunk is
     // all in or all out.  Out-of-range chunks are pointed at kOob and fetch nothing.
+    //
+    // Two ways of fetching a tile.  By halves (two rank slices): lane (li, g) loads what operand
+    // (rt, s) wants from it, row li, chunk (s, g): four lanes and 64 bytes per row and
+    // instruction; the registers of half s are refilled as soon as its MFMAs are issued.  By
+    // lines (one rank slice): eight rows x 128 bytes per instruction, which the load path moves
+    // faster: in load x = 2 rt + h of a tile lane (li, g) takes row 16 rt + 8 h + li % 8, chunk
+    // (li / 8, g), which leaves the lanes li < 8 of load 2 rt and the lanes li >= 8 of load
+    // 2 rt + 1 holding what operand (rt, s) wants for s = 0 and 1, and the other halves each
+    // other's; settle_tile swaps those within each row of 16 lanes (two DPP moves per register
+    // pair).  All loads of a tile are then refilled together, which keeps less in flight: with
+    // two rank slices, where every byte passes the load path twice, that costs more than the
+    // whole lines gain (workload 4: 2.70 against 2.31 ms), with one it wins (workload 3: 54
+    // against 64 us).
+    constexpr bool kLines = ONCE;
+    uint32_t lane_off[2 * RT];
+#pragma unroll
+    for (int x = 0; x < 2 * RT; ++x)
+        lane_off[x] = kLines ? ((uint32_t)(8 * x + (li & 7)) * (uint32_t)m + 8u * (uint32_t)(g + 4 * (li >> 3))) * 2u
+                             : ((uint32_t)(16 * (x >> 1) + li) * (uint32_t)m + 8u * (uint32_t)g) * 2u;
     auto load_half = [&](v4u (&dst)[RT][2], int tile, int s) {
         const uint32_t col = (uint32_t)tile * kWBK + 32u * (uint32_t)s + 8u * (uint32_t)g;
         const bool ok = col < (uint32_t)col_end;
         const uint32_t coff = ((uint32_t)tile * kWBK + 32u * (uint32_t)s) * 2u;
 #pragma unroll
-        // with one rank slice G is read once by the launch and streamed; with two, the second
-        // slice must find it in L2
-        for (int rt = 0; rt < RT; ++rt) dst[rt][s] = buf_load_u4<ONCE>(rs, ok ? lane_off[rt] + coff : kOob);
+        for (int rt = 0; rt < RT; ++rt) dst[rt][s] = buf_load_u4<ONCE>(rs, ok ? lane_off[2 * rt] + coff : kOob);
+    };
+    auto load_tile = [&](v4u (&dst)[RT][2], int tile) {
+        if (!kLines) {
+            load_half(dst, tile, 0);
+            load_half(dst, tile, 1);
+            return;
+        }
+        const uint32_t col = (uint32_t)tile * kWBK + 8u * (uint32_t)(g + 4 * (li >> 3));
+        const bool ok = col < (uint32_t)col_end;
+        const uint32_t coff = (uint32_t)tile * kWBK * 2u;
+#pragma unroll
+        for (int x = 0; x < 2 * RT; ++x) dst[x >> 1][x & 1] = buf_load_u4<ONCE>(rs, ok ? lane_off[x] + coff : kOob);
+    };
+    auto settle_tile = [&](v4u (&t)[RT][2]) {
+        if (!kLines) return;
+        constexpr int kRor8 = 0x128;          // DPP row_ror:8: lane li of a row of 16 reads lane li ^ 8
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t lo = t[rt][0][c], hi = t[rt][1][c];
+                // s = 0: lanes li >= 8 (banks 2, 3) take load 2 rt + 1's lanes li - 8
+                t[rt][0][c] = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)hi, kRor8, 0xf, 0xc, false);
+                // s = 1: lanes li < 8 (banks 0, 1) take load 2 rt's lanes li + 8
+                t[rt][1][c] = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)lo, kRor8, 0xf, 0x3, false);
+            }
     };
 
     // 64 x RS normals per tile = 16 RS quads, NQ per thread: thread p takes quad index
@@ -333,6 +372,7 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     // ct multiplies.  As soon as the MFMAs of a half are issued its registers are refilled
     // with the tile two steps ahead.
     auto mfma_tile = [&](v4u (&gt)[RT][2], int buf, int tile) {
+        settle_tile(gt);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             if (MAP == 1) {      // the statistic's term: G squared in fp32, rounded back to bf16
@@ -353,11 +393,8 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
                 bv = bn;
             }
             __builtin_amdgcn_sched_barrier(0);
-            // Streamed loads are not kept in L2: the two 64-byte halves of a row's 128-byte line
-            // are then asked for together, at the end of the tile, or the second would often
-            // fetch the line from memory again.
-            if (!ONCE) load_half(gt, tile + 2, s);
-            else if (s == 1) { load_half(gt, tile + 2, 0); load_half(gt, tile + 2, 1); }
+            if (!kLines) load_half(gt, tile + 2, s);
+            else if (s == 1) load_tile(gt, tile + 2);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -375,10 +412,8 @@ __global__ __launch_bounds__(512) void compress_bf16_wide_kernel(const MatDev* _
     };
 
     v4u gx[RT][2], gy[RT][2];
-    load_half(gx, tile0, 0);
-    load_half(gx, tile0, 1);
-    load_half(gy, tile0 + 1, 0);
-    load_half(gy, tile0 + 1, 1);
+    load_tile(gx, tile0);
+    load_tile(gy, tile0 + 1);
     gen_tile(0, tile0);
     gen_if(early, 1, tile0 + 1);
     __syncthreads();
