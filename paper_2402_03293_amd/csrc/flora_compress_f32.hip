@@ -121,26 +121,62 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
         valid = valid < 0 ? 0 : (valid > 16 ? 16 : valid);
         rs[mt] = make_rsrc(G + (first < n ? first : 0) * m, valid * m * ESZ);
     }
-    const uint32_t lane_off = ((uint32_t)li * (uint32_t)m + 4u * (uint32_t)g) * ESZ;
+    // fp32 gradients are fetched eight rows x 128 bytes per instruction (whole lines, which the
+    // load path moves faster than the 16 rows x 64 bytes the operand layout asks for): load
+    // (h, L) of a 16-row block takes, in lane (li, g), row 8 h + li % 8 and the 16 bytes at column
+    // 32 L + 16 (li / 8) + 4 g.  The lanes li < 8 of load (0, L) and the lanes li >= 8 of load
+    // (1, L) then hold what operand registers c = 2 L and c = 2 L + 1 want, and the other halves
+    // each other's: settle_tile swaps those within each row of 16 lanes with DPP moves, right
+    // before the tile multiplies.  bf16 gradients (8 bytes per lane) keep the direct pattern.
+    constexpr bool kLines = ESZ == 4;
+    const uint32_t lane_off = kLines ? ((uint32_t)(li & 7) * (uint32_t)m + 4u * (uint32_t)g + 16u * (uint32_t)(li >> 3)) * ESZ
+                                     : ((uint32_t)li * (uint32_t)m + 4u * (uint32_t)g) * ESZ;
 
     auto load_tile_fast = [&](v4f (&dst)[MT][4], int i) {
         const int tile = tbase + kg + KG * i;
         // a round past the end has a tile past the last one, so its columns fail the same test
-        const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g;
+        if constexpr (kLines) {
+            const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g + 16u * (uint32_t)(li >> 3);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const bool ok = col0 + 16u * c < (uint32_t)col_end;
-            const uint32_t off = ok ? lane_off + ((uint32_t)tile * kBK + 16u * c) * ESZ : kOob;
+            for (int L = 0; L < 2; ++L) {
+                const bool ok = col0 + 32u * L < (uint32_t)col_end;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                if (ESZ == 4) {
-                    dst[mt][c] = buf_load_f4<true>(rs[mt], off);      // G is read once: streamed
-                } else {
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t off = ok ? lane_off + (8u * h * (uint32_t)m + (uint32_t)tile * kBK + 32u * L) * ESZ : kOob;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) dst[mt][2 * L + h] = buf_load_f4<true>(rs[mt], off);   // G is read once: streamed
+                }
+            }
+        } else {
+            const uint32_t col0 = (uint32_t)tile * kBK + 4u * (uint32_t)g;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool ok = col0 + 16u * c < (uint32_t)col_end;
+                const uint32_t off = ok ? lane_off + ((uint32_t)tile * kBK + 16u * c) * ESZ : kOob;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
                     const v2u p2 = buf_load_u2<true>(rs[mt], off);
                     dst[mt][c] = v4f{bf16_bits_to_f32(p2.x & 0xffffu), bf16_bits_to_f32(p2.x >> 16),
                                      bf16_bits_to_f32(p2.y & 0xffffu), bf16_bits_to_f32(p2.y >> 16)};
                 }
             }
+        }
+    };
+    auto settle_tile = [&](v4f (&t)[MT][4]) {
+        if constexpr (kLines) {
+            constexpr int kRor8 = 0x128;      // DPP row_ror:8: lane li of a row of 16 reads lane li ^ 8
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int L = 0; L < 2; ++L)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int lo = __float_as_int(t[mt][2 * L][e]), hi = __float_as_int(t[mt][2 * L + 1][e]);
+                        // c = 2 L: lanes li >= 8 (banks 2, 3) take load (1, L)'s lanes li - 8
+                        t[mt][2 * L][e] = __int_as_float(__builtin_amdgcn_update_dpp(lo, hi, kRor8, 0xf, 0xc, false));
+                        // c = 2 L + 1: lanes li < 8 (banks 0, 1) take load (0, L)'s lanes li + 8
+                        t[mt][2 * L + 1][e] = __int_as_float(__builtin_amdgcn_update_dpp(hi, lo, kRor8, 0xf, 0x3, false));
+                    }
         }
     };
 
@@ -183,7 +219,8 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
             }
         }
 
-    auto mfma_tile = [&](const v4f (&gt)[MT][4], int buf) {
+    auto mfma_tile = [&](v4f (&gt)[MT][4], int buf, bool settle) {
+        if (settle) settle_tile(gt);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             v4f bv[NT];
@@ -223,7 +260,7 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
                 const int buf = i & 1;
                 load_tile_fast(st[(u + kPF - 1) % kPF], i + kPF - 1);
                 if (i + 1 < fast_rounds) gen_tile(buf ^ 1, i + 1);
-                mfma_tile(st[u], buf);
+                mfma_tile(st[u], buf, true);
                 __syncthreads();
             }
         }
@@ -241,7 +278,7 @@ __global__ __launch_bounds__(256 * KG) void compress_f32_kernel(const MatDev* __
             gen_tile(0, i);
         }
         __syncthreads();
-        if (active) mfma_tile(gt, 0);
+        if (active) mfma_tile(gt, 0, false);
         __syncthreads();
     }
 
