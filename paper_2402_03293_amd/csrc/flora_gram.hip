@@ -10,17 +10,25 @@
 // precision of the decompression itself: A and S are rounded to bf16 exactly as the update pass
 // rounds them, the Gram matrices are accumulated in fp32 and rounded to bf16 once.
 //
-// gram_kernel: one workgroup sums X_t X_t^T over a chunk of the long index t (X_t = row t of A,
-//   regenerated, optionally scaled by 1 / sqrt(K_t); or row t of S, loaded) into a partial r x r
-//   matrix; tiles of 64 t are staged in LDS transposed ([k][t], bf16), both MFMA operands come
-//   from there.  combine_gram_kernel adds the chunks' partials in chunk order and stores the
-//   result as bf16 in the arrangement quadform_kernel copies into LDS.
-// quadform_kernel: q_i = Z_i B Z_i^T for a block of rows of Z (rows of S, loaded; or rows of A,
-//   regenerated), B a Gram matrix held in LDS.  The product is taken transposed,
+// What the kernels cost is regenerating A (the vector ALU), so the sums are ordered to sweep A
+// twice, not three times: Q from one read of S and the column statistics K from a sweep over
+// generated rows of A; then ONE further sweep over A yields both P and P'; then the row statistics
+// R and the clipping sum from a read of S each.
+//
+// gram_sym_kernel (ranks >= 128) / gram_kernel (rank 64): one workgroup sums X_t X_t^T over a chunk
+//   of the long index t (X_t = row t of A, regenerated, plain and scaled with 1 / K_t; or row t of
+//   S, loaded) into partial r x r matrices; tiles of 64 t are staged in LDS transposed ([k][t],
+//   bf16), both MFMA operands come from there.  combine_gram_kernel adds the chunks' partials in
+//   chunk order and stores the result as bf16 in the arrangement the quadratic-form kernel that
+//   reads it copies into LDS.
+// quadform_kernel: q_i = Z_i B Z_i^T for a block of rows of Z (rows of S, loaded; at rank 64 also
+//   rows of A, regenerated), B a Gram matrix held in LDS.  The product is taken transposed,
 //   D[k2][i] = sum_k1 B[k2][k1] Z[i][k1], so that lane (i, g) ends up with D[16 c + 4 g + v][i]; the
 //   contraction order over k1 is free, and it is chosen so that the same lane's operand
 //   registers hold exactly Z[i][16 c + 4 g + v]: q_i is then a dot product of registers the lane
-//   already has, summed over the four lanes that share a row.
+//   already has, summed over the four lanes that share a row.  quadform_cols_kernel (ranks >= 128)
+//   is the same scheme on 32 x 32 x 16 tiles for rows of A generated into the operand registers.
+//   The kernels finish the statistics themselves (R_i, K_j, one partial sum of R per row block).
 #include <type_traits>
 
 #include "flora_gen.hip.h"
