@@ -63,6 +63,10 @@ def parse_args():
                          "(beta 0.9) and update from that.  folded: accumulate into C under one projection, "
                          "then M <- beta M + ((1-beta)/tau) C A_c^T A_m (flora_transfer_accumulate); direct: one "
                          "projection for both, every micro-batch is compressed straight into M")
+    ap.add_argument("--rank", type=int, default=None, choices=[8, 16, 32, 64, 128, 256],
+                    help="run the configuration's shapes at another rank (a variant, named as such in config.workload)")
+    ap.add_argument("--grad-dtype", default=None, choices=["f32", "bf16"],
+                    help="run the configuration's shapes with gradients of another type (a variant)")
     ap.add_argument("--weights", default="f32", choices=["f32", "bf16"],
                     help="dtype of the weights (the workloads are defined with fp32 weights; bf16 weights are "
                          "updated in fp32 and rounded to nearest even when stored)")
@@ -190,6 +194,10 @@ def run_config(args, index, steps, warmup, cpu_seconds, variants=True):
 
     dev = "cuda:0"
     wl = workloads.workload(index)
+    if variants and (args.rank or args.grad_dtype):
+        import dataclasses
+        wl = dataclasses.replace(wl, r=args.rank or wl.r, grad_dtype=args.grad_dtype or wl.grad_dtype,
+                                 name="%s-shapes-%s-r%d" % (wl.name, args.grad_dtype or wl.grad_dtype, args.rank or wl.r))
     r = wl.r
     shapes = wl.shapes
     count = len(shapes)
